@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the DiT denoising-step attention path on one MI355X.
+
+A "step" is one dit_attn_varlen_fwd call (the whole hot path: work-list, K/V streaming, both MFMA
+contractions, online softmax, epilogue) over one packed synthetic batch that is already resident in HBM.
+Prints ONE JSON line.  `value` is attention TFLOP/s (4*H*D*sum L_i^2 flops per call / time per call).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline] [--all]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from dit_workloads import CONFIG_NAMES, attention_flops, make_workload, sample_rows  # noqa: E402
+
+# AMD's published dense bf16 matrix peak for MI355X: 256 CUs x 4096 flop/clk/CU x 2.4 GHz.
+MFMA_BF16_PEAK_TFLOPS = 2516.6
+DEFAULT_WORKLOAD = "mixed_varlen"
+
+
+def _to_dev(bits, torch):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to("cuda").view(torch.bfloat16)
+
+
+def time_workload(da, torch, ctx, w, steps: int, warmup: int):
+    """Returns (wall ms per step, mean kernel ms from per-step event pairs, list of per-step ms, out tensor)."""
+    q, k, v = _to_dev(w.q, torch), _to_dev(w.k, torch), _to_dev(w.v, torch)
+    out = torch.empty_like(q)
+    stream = torch.cuda.current_stream().cuda_stream
+    H, D = w.n_heads, w.head_dim
+
+    def step():
+        da.dit_attn_varlen_fwd(ctx, q, k, v, w.cu_seqlens, H, D, w.scale, out, stream)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record()  # events sit on torch's current stream, the stream the kernel is launched on
+        step()
+        ends[i].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per = [s.elapsed_time(e) for s, e in zip(starts, ends)]
+    return (t1 - t0) * 1e3 / steps, float(np.mean(per)), per, out
+
+
+def cpu_baseline(w, budget_s: float = 20.0):
+    """The fp64 oracle, as it stands, on a bounded row sample of the same workload."""
+    from oracle import dit_attn_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    lens = np.diff(w.cu_seqlens)
+    # calibrate on a few rows, then size the sample to the budget
+    rows = sample_rows(w.cu_seqlens, seed=w.seed, block=64, max_rows=24)
+    t0 = time.perf_counter()
+    orc.attention_varlen_rows(w.q, w.k, w.v, w.cu_seqlens, w.scale, rows)
+    t_cal = time.perf_counter() - t0
+    n_rows = int(min(max(24, len(rows) * budget_s / max(t_cal, 1e-3)), 4096, w.total_tokens))
+    rows = sample_rows(w.cu_seqlens, seed=w.seed + 1, block=64, max_rows=n_rows)
+    t0 = time.perf_counter()
+    orc.attention_varlen_rows(w.q, w.k, w.v, w.cu_seqlens, w.scale, rows)
+    dt = time.perf_counter() - t0
+    seq_of = np.searchsorted(w.cu_seqlens, rows, side="right") - 1
+    flops = 4.0 * w.n_heads * w.head_dim * float(np.sum(lens[seq_of].astype(np.float64)))
+    return {
+        "value": flops / dt / 1e12,
+        "unit": "TFLOP/s",
+        "cores": int(threads),
+        "kind": "oracle",
+        "sample": f"{len(rows)} stratified query rows x {w.n_heads} heads of {w.name}, all keys each, "
+                  f"{dt:.1f} s; full call extrapolates to {attention_flops(w.cu_seqlens, w.n_heads, w.head_dim) / (flops / dt):.0f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=CONFIG_NAMES)
+    ap.add_argument("--all", action="store_true", help="also time the other configurations (reported under per_config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2604_04335_amd as da
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    da.load_library()
+    torch.cuda.set_device(0)
+    ctx = da.dit_attn_create(0)
+
+    w = make_workload(args.workload, args.seed)
+    flops = attention_flops(w.cu_seqlens, w.n_heads, w.head_dim)
+    wall_ms, kern_ms, per, _ = time_workload(da, torch, ctx, w, args.steps, args.warmup)
+    tflops = flops / (wall_ms * 1e-3) / 1e12
+    kern_tflops = flops / (kern_ms * 1e-3) / 1e12
+
+    result = {
+        "metric": "DiT attention TFLOP/s per denoising step (bf16) and % of MFMA peak, 1 GPU",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name,
+            "seq_lens": w.seq_lens,
+            "n_heads": w.n_heads,
+            "head_dim": w.head_dim,
+            "total_tokens": w.total_tokens,
+            "tflop_per_call": round(flops / 1e12, 4),
+            "seed": w.seed,
+        },
+        "pct_of_mfma_peak": round(100.0 * tflops / MFMA_BF16_PEAK_TFLOPS, 2),
+        "step_ms_min": round(float(np.min(per)), 4),
+        "step_ms_cv_pct": round(100.0 * float(np.std(per) / np.mean(per)), 3),
+        "roofline": {
+            "bound": "mfma",
+            "kernel": "attn_fwd_kernel",
+            "achieved": round(kern_tflops, 2),
+            "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(kern_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+            "traffic": None,
+            "kernel_ms_avg": round(kern_ms, 4),
+            "algorithmic_hbm_bytes": int(4 * w.total_tokens * w.n_heads * w.head_dim * 2),
+        },
+    }
+
+    if args.all:
+        per_cfg = {}
+        for name in CONFIG_NAMES:
+            if name == w.name:
+                per_cfg[name] = {"ms": round(kern_ms, 4), "tflops": round(kern_tflops, 2)}
+                continue
+            w2 = make_workload(name)
+            f2 = attention_flops(w2.cu_seqlens, w2.n_heads, w2.head_dim)
+            _, k2, _, _ = time_workload(da, torch, ctx, w2, max(5, args.steps // 2), 3)
+            per_cfg[name] = {"ms": round(k2, 4), "tflops": round(f2 / (k2 * 1e-3) / 1e12, 2),
+                             "pct_of_mfma_peak": round(100.0 * f2 / (k2 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
+            del w2
+        result["per_config"] = per_cfg
+
+    da.dit_attn_destroy(ctx)
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w)
+    else:
+        result["cpu_baseline"] = None
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

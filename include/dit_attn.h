@@ -1,0 +1,137 @@
+/*
+ * dit_attn.h - C ABI of the MI355X (gfx950) DiT denoising-step self-attention.
+ *
+ * One call computes, for a packed batch of independent token sequences, the
+ * self-attention of a DiT block during one denoising step:
+ *
+ *     for every sequence i with rows R_i = [cu_seqlens[i], cu_seqlens[i+1]),
+ *     every head h and every query row r in R_i:
+ *         O[r,h,:] = sum_{j in R_i} softmax_j( scale * <Q[r,h,:], K[j,h,:]> ) * V[j,h,:]
+ *
+ * The batch is what the paper's serving loop hands to a GPU for one step:
+ * same-resolution image requests coalesced into one call (paper Section 4.3,
+ * "SLO-aware Dynamic Batching"), a whole video request (Section 4.4, one
+ * request per GPU set), or one GPU's head subset of a sequence-parallel video
+ * (Section 5, Unified Sequence Parallel attention; Section 4.3, "Elastic
+ * Sequence Parallelism").  Attention is bidirectional inside a sequence and
+ * never crosses sequences.  Text and latent tokens are ordinary rows.
+ *
+ * Precision: bf16 inputs, fp32 scores / softmax state / accumulators, the
+ * probabilities are rounded to bf16 (nearest-even) before the second
+ * contraction, bf16 output (nearest-even).
+ *
+ * All functions are thread-compatible, not thread-safe: one context must not
+ * be used from two host threads, or for two streams, at the same time.
+ * No C++ exception crosses this boundary.
+ */
+#ifndef DIT_ATTN_H_
+#define DIT_ATTN_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Return codes. */
+#define DIT_ATTN_OK                 0
+#define DIT_ATTN_ERR_NULL          (-1)  /* a required pointer is NULL */
+#define DIT_ATTN_ERR_HEAD_DIM      (-2)  /* head_dim is not 64 or 128 */
+#define DIT_ATTN_ERR_CU_SEQLENS    (-3)  /* cu_seqlens[0] != 0, decreasing, or n_seqs < 0 */
+#define DIT_ATTN_ERR_HIP           (-4)  /* a HIP runtime call failed; see dit_attn_last_error */
+#define DIT_ATTN_ERR_SCALE         (-5)  /* scale is NaN or infinite */
+#define DIT_ATTN_ERR_N_HEADS       (-6)  /* n_heads < 1 or > 65535 */
+#define DIT_ATTN_ERR_ALIGN         (-7)  /* q, k, v or out is not 16-byte aligned */
+#define DIT_ATTN_ERR_CAPACITY      (-8)  /* output buffer of dit_attn_plan too small */
+
+typedef struct dit_attn_ctx dit_attn_ctx; /* opaque */
+
+/*
+ * Create a context bound to HIP device `device_id` (host call).
+ * The context owns a small amount of device memory: cached work-lists (one per
+ * distinct (cu_seqlens, n_heads, head_dim) seen, 16 bytes per work item) and a
+ * work counter.  *out_ctx is written only on success.
+ * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL, or DIT_ATTN_ERR_HIP (no such device,
+ * not a gfx950 device, allocation failure).
+ */
+int dit_attn_create(dit_attn_ctx** out_ctx, int device_id);
+
+/*
+ * One denoising-step attention call over a packed variable-length batch
+ * (paper Sections 4.3 and 5; the math is the definition at the top of this file).
+ *
+ *   q, k, v     DEVICE pointers, bf16, shape [T, n_heads, head_dim], contiguous
+ *               (row stride n_heads*head_dim elements), T = cu_seqlens[n_seqs].
+ *               16-byte aligned.  Read only.
+ *   cu_seqlens  HOST pointer, n_seqs + 1 int32 entries, cu_seqlens[0] == 0,
+ *               non-decreasing.  Read during the call only (the batch is formed
+ *               by host code, which knows the lengths).  Zero-length sequences
+ *               are legal and contribute no rows.
+ *   n_seqs      number of sequences, >= 0.  n_seqs == 0 or T == 0: returns
+ *               DIT_ATTN_OK and launches nothing.
+ *   n_heads     heads in q, k and v alike (no grouped-query sharing), 1..65535.
+ *   head_dim    64 or 128.
+ *   scale       multiplies the fp32 scores before the softmax; any finite value
+ *               (zero and negative included).
+ *   out         DEVICE pointer, bf16, same shape and layout as q; must not
+ *               overlap q, k or v.  Exactly the rows [0, T) are written.
+ *   stream      a hipStream_t (as void*); NULL is the default stream.
+ *
+ * The work is enqueued on `stream`; the call does not synchronise.  The first
+ * call with a new (cu_seqlens, n_heads, head_dim) builds a work-list on the host
+ * and uploads it (one device allocation and one stream-ordered copy); later
+ * calls with the same pack reuse it and do no host work beyond a compare.
+ * The caller keeps ownership of every buffer.  Validation precedes any launch:
+ * on a non-zero return `out` is untouched.
+ */
+int dit_attn_varlen_fwd(dit_attn_ctx* ctx,
+                        const void* q, const void* k, const void* v,
+                        const int32_t* cu_seqlens, int32_t n_seqs,
+                        int32_t n_heads, int32_t head_dim, float scale,
+                        void* out, void* stream);
+
+/*
+ * Destroy a context and free its device memory (host call).  The caller must
+ * have synchronised every stream the context was used on.  NULL is a no-op.
+ */
+void dit_attn_destroy(dit_attn_ctx* ctx);
+
+/*
+ * Text of the last error recorded in `ctx` (or of the last failed
+ * dit_attn_create when ctx is NULL).  The string is owned by the library and
+ * valid until the next call on the same context.
+ */
+const char* dit_attn_last_error(const dit_attn_ctx* ctx);
+
+/*
+ * Host-only: the work-list that dit_attn_varlen_fwd would run for this pack,
+ * in execution order (paper Section 4.3: a batch mixes requests of different
+ * lengths; the list balances their tiles over compute units by handing out the
+ * costliest items first).  Needs no GPU and no context.
+ *
+ * Each item is one (sequence, head, query tile): 4 int32 values
+ *     [0] q_start   first global query row of the tile
+ *     [1] kv_start  first global key row (= start of the tile's sequence)
+ *     [2] kv_len    number of keys (= length of the sequence)
+ *     [3] (q_rows << 16) | head     q_rows in 1..block_m
+ * Query tiles start at the sequence start (not at multiples of block_m of the
+ * global row index), so a sequence's result does not depend on what it is
+ * packed with.
+ *
+ *   items      HOST output buffer of capacity_items * 4 int32, may be NULL when
+ *              capacity_items == 0 (to query the count).
+ *   block_m    out: query rows per tile used for this head_dim.
+ *   returns    the number of items (>= 0), or a negative error code;
+ *              DIT_ATTN_ERR_CAPACITY if capacity_items > 0 is too small.
+ */
+int64_t dit_attn_plan(const int32_t* cu_seqlens, int32_t n_seqs,
+                      int32_t n_heads, int32_t head_dim,
+                      int32_t* items, int64_t capacity_items, int32_t* block_m);
+
+/* Library version string, e.g. "dit_attn 0.1 gfx950". */
+const char* dit_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIT_ATTN_H_ */

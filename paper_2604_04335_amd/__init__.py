@@ -1,0 +1,195 @@
+"""Python binding of the MI355X DiT denoising-step attention library.
+
+Argument marshalling only: every step of the computation runs in the HIP
+kernels behind the C ABI declared in include/dit_attn.h.  PyTorch is used by
+callers for device memory and streams; this module itself only needs ctypes
+and numpy, and accepts anything with `data_ptr()` (torch tensors) or a raw
+integer device address.
+
+There is no CPU fallback: if the shared library has not been built
+(`python -m paper_2604_04335_amd.build`) importing the symbols raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+__all__ = [
+    "DitAttnError",
+    "lib_path",
+    "load_library",
+    "dit_attn_version",
+    "dit_attn_create",
+    "dit_attn_varlen_fwd",
+    "dit_attn_destroy",
+    "dit_attn_last_error",
+    "dit_attn_plan",
+    "DitAttention",
+]
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+ERROR_NAMES = {
+    0: "DIT_ATTN_OK",
+    -1: "DIT_ATTN_ERR_NULL",
+    -2: "DIT_ATTN_ERR_HEAD_DIM",
+    -3: "DIT_ATTN_ERR_CU_SEQLENS",
+    -4: "DIT_ATTN_ERR_HIP",
+    -5: "DIT_ATTN_ERR_SCALE",
+    -6: "DIT_ATTN_ERR_N_HEADS",
+    -7: "DIT_ATTN_ERR_ALIGN",
+    -8: "DIT_ATTN_ERR_CAPACITY",
+}
+
+
+class DitAttnError(RuntimeError):
+    def __init__(self, code: int, message: str = ""):
+        self.code = code
+        super().__init__(f"{ERROR_NAMES.get(code, code)}: {message}")
+
+
+def lib_path() -> str:
+    return os.path.join(_PKG_DIR, "libdit_attn.so")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libdit_attn.so (built in-tree).  Raises if it is missing: there is no fallback."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing; build it with `python -m paper_2604_04335_amd.build`")
+    lib = ctypes.CDLL(path)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.dit_attn_version.restype = ctypes.c_char_p
+    lib.dit_attn_version.argtypes = []
+    lib.dit_attn_create.restype = ctypes.c_int
+    lib.dit_attn_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int]
+    lib.dit_attn_varlen_fwd.restype = ctypes.c_int
+    lib.dit_attn_varlen_fwd.argtypes = [vp, vp, vp, vp, i32p, i32, i32, i32, ctypes.c_float, vp, vp]
+    lib.dit_attn_destroy.restype = None
+    lib.dit_attn_destroy.argtypes = [vp]
+    lib.dit_attn_last_error.restype = ctypes.c_char_p
+    lib.dit_attn_last_error.argtypes = [vp]
+    lib.dit_attn_plan.restype = i64
+    lib.dit_attn_plan.argtypes = [i32p, i32, i32, i32, i32p, i64, i32p]
+    _LIB = lib
+    return lib
+
+
+def _ptr(x) -> int:
+    if x is None:
+        return 0
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr())
+    return int(x)
+
+
+def _cu_array(cu_seqlens) -> np.ndarray:
+    if hasattr(cu_seqlens, "detach"):  # torch tensor: must live on the host
+        if cu_seqlens.device.type != "cpu":
+            raise ValueError("cu_seqlens must be a host array")
+        cu_seqlens = cu_seqlens.detach().numpy()
+    return np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+
+
+def dit_attn_version() -> str:
+    return load_library().dit_attn_version().decode()
+
+
+def dit_attn_last_error(ctx) -> str:
+    return load_library().dit_attn_last_error(ctypes.c_void_p(ctx or 0)).decode()
+
+
+def dit_attn_create(device_id: int = 0) -> int:
+    """Returns an opaque context handle (an integer address)."""
+    lib = load_library()
+    h = ctypes.c_void_p()
+    rc = lib.dit_attn_create(ctypes.byref(h), int(device_id))
+    if rc != 0:
+        raise DitAttnError(rc, dit_attn_last_error(None))
+    return int(h.value)
+
+
+def dit_attn_destroy(ctx) -> None:
+    if ctx:
+        load_library().dit_attn_destroy(ctypes.c_void_p(ctx))
+
+
+def dit_attn_varlen_fwd(ctx, q, k, v, cu_seqlens, n_heads: int, head_dim: int, scale: float, out, stream=None,
+                        n_seqs: int | None = None) -> None:
+    """One denoising-step attention call; see include/dit_attn.h.
+
+    q, k, v, out: device buffers (torch tensors or integer addresses), bf16 [T, n_heads, head_dim].
+    cu_seqlens: host int32 sequence of n_seqs + 1 offsets.  stream: integer hipStream_t or None.
+    Raises DitAttnError on a non-zero return code.
+    """
+    lib = load_library()
+    cu = _cu_array(cu_seqlens)
+    if n_seqs is None:
+        n_seqs = len(cu) - 1
+    rc = lib.dit_attn_varlen_fwd(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(q)), ctypes.c_void_p(_ptr(k)),
+                                 ctypes.c_void_p(_ptr(v)), cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                 int(n_seqs), int(n_heads), int(head_dim), float(scale),
+                                 ctypes.c_void_p(_ptr(out)), ctypes.c_void_p(_ptr(stream)))
+    if rc != 0:
+        raise DitAttnError(rc, dit_attn_last_error(ctx))
+
+
+def dit_attn_plan(cu_seqlens, n_heads: int, head_dim: int):
+    """Host-only: the ordered work-list as an int32 array [n_items, 4] and the tile height block_m."""
+    lib = load_library()
+    cu = _cu_array(cu_seqlens)
+    n_seqs = len(cu) - 1
+    cu_p = cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    bm = ctypes.c_int32(0)
+    n = lib.dit_attn_plan(cu_p, n_seqs, int(n_heads), int(head_dim), None, 0, ctypes.byref(bm))
+    if n < 0:
+        raise DitAttnError(int(n), "dit_attn_plan")
+    items = np.zeros((max(int(n), 1), 4), dtype=np.int32)
+    n2 = lib.dit_attn_plan(cu_p, n_seqs, int(n_heads), int(head_dim),
+                           items.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), int(items.shape[0]), ctypes.byref(bm))
+    if n2 < 0:
+        raise DitAttnError(int(n2), "dit_attn_plan")
+    return items[:int(n2)], int(bm.value)
+
+
+class DitAttention:
+    """Owns one context; `forward` takes torch tensors and uses torch's current stream."""
+
+    def __init__(self, device_id: int = 0):
+        self.device_id = int(device_id)
+        self.ctx = dit_attn_create(self.device_id)
+
+    def forward(self, q, k, v, cu_seqlens, scale: float | None = None, out=None, stream=None):
+        import torch  # device memory and streams only
+
+        T, H, D = q.shape
+        assert q.dtype == torch.bfloat16 and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+        assert k.shape == q.shape and v.shape == q.shape
+        if out is None:
+            out = torch.empty_like(q)
+        if scale is None:
+            scale = float(D) ** -0.5
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device).cuda_stream
+        dit_attn_varlen_fwd(self.ctx, q, k, v, cu_seqlens, H, D, scale, out, stream)
+        return out
+
+    __call__ = forward
+
+    def close(self):
+        if self.ctx:
+            dit_attn_destroy(self.ctx)
+            self.ctx = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

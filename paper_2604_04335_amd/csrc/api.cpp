@@ -1,0 +1,273 @@
+// C ABI of the DiT denoising-step attention library: argument checks, plan cache, launch.
+#include "../../include/dit_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "attn_fwd.h"
+#include "plan.h"
+
+namespace {
+
+struct CachedPlan {
+  std::vector<int32_t> cu;  // key: cu_seqlens contents
+  int32_t n_heads = 0;
+  int32_t head_dim = 0;
+  std::vector<dit::WorkItem> host_items;  // kept alive: source of the stream-ordered upload
+  dit::WorkItem* dev_items = nullptr;
+  uint64_t last_use = 0;
+};
+
+constexpr size_t kMaxCachedPlans = 32;
+constexpr size_t kMaxItems = size_t(1) << 30;
+
+thread_local std::string g_create_error;
+
+}  // namespace
+
+struct dit_attn_ctx {
+  int device = 0;
+  int n_cus = 0;
+  uint32_t* counter = nullptr;  // device; value is tracked on the host in counter_value
+  uint32_t counter_value = 0;
+  uint64_t tick = 0;
+  std::vector<std::unique_ptr<CachedPlan>> plans;
+  std::string error;
+};
+
+namespace {
+
+int fail(dit_attn_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->error = msg;
+  return code;
+}
+
+int fail_hip(dit_attn_ctx* ctx, hipError_t e, const char* what) {
+  // Clear the sticky error so that it is not reported by an unrelated later call.
+  (void)hipGetLastError();
+  return fail(ctx, DIT_ATTN_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+struct DeviceGuard {
+  int prev = -1;
+  bool switched = false;
+  hipError_t enter(int dev) {
+    hipError_t e = hipGetDevice(&prev);
+    if (e != hipSuccess) return e;
+    if (prev != dev) {
+      e = hipSetDevice(dev);
+      if (e != hipSuccess) return e;
+      switched = true;
+    }
+    return hipSuccess;
+  }
+  ~DeviceGuard() {
+    if (switched) (void)hipSetDevice(prev);
+  }
+};
+
+int check_shape_args(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int32_t head_dim, std::string& msg) {
+  if (!cu_seqlens) {
+    msg = "cu_seqlens is NULL";
+    return DIT_ATTN_ERR_NULL;
+  }
+  if (head_dim != 64 && head_dim != 128) {
+    msg = "head_dim must be 64 or 128, got " + std::to_string(head_dim);
+    return DIT_ATTN_ERR_HEAD_DIM;
+  }
+  if (n_heads < 1 || n_heads > 65535) {
+    msg = "n_heads must be in 1..65535, got " + std::to_string(n_heads);
+    return DIT_ATTN_ERR_N_HEADS;
+  }
+  if (dit::plan_validate(cu_seqlens, n_seqs) != 0) {
+    msg = "cu_seqlens must start at 0 and be non-decreasing, n_seqs >= 0";
+    return DIT_ATTN_ERR_CU_SEQLENS;
+  }
+  return DIT_ATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dit_attn_version(void) { return "dit_attn 0.1 gfx950"; }
+
+int dit_attn_create(dit_attn_ctx** out_ctx, int device_id) {
+  if (!out_ctx) {
+    g_create_error = "out_ctx is NULL";
+    return DIT_ATTN_ERR_NULL;
+  }
+  int n_dev = 0;
+  hipError_t e = hipGetDeviceCount(&n_dev);
+  if (e != hipSuccess || device_id < 0 || device_id >= n_dev) {
+    (void)hipGetLastError();
+    g_create_error = "no HIP device " + std::to_string(device_id) + " (" +
+                     (e != hipSuccess ? hipGetErrorString(e) : "device count " + std::to_string(n_dev)) + ")";
+    return DIT_ATTN_ERR_HIP;
+  }
+  hipDeviceProp_t prop;
+  e = hipGetDeviceProperties(&prop, device_id);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    g_create_error = std::string("hipGetDeviceProperties: ") + hipGetErrorString(e);
+    return DIT_ATTN_ERR_HIP;
+  }
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+    g_create_error = std::string("device is ") + prop.gcnArchName + ", this library holds gfx950 code only";
+    return DIT_ATTN_ERR_HIP;
+  }
+  dit_attn_ctx* ctx = new (std::nothrow) dit_attn_ctx();
+  if (!ctx) {
+    g_create_error = "out of host memory";
+    return DIT_ATTN_ERR_HIP;
+  }
+  ctx->device = device_id;
+  ctx->n_cus = prop.multiProcessorCount;
+  DeviceGuard guard;
+  e = guard.enter(device_id);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->counter), sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMemset(ctx->counter, 0, sizeof(uint32_t));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    g_create_error = std::string("context set-up: ") + hipGetErrorString(e);
+    if (ctx->counter) (void)hipFree(ctx->counter);
+    delete ctx;
+    return DIT_ATTN_ERR_HIP;
+  }
+  *out_ctx = ctx;
+  return DIT_ATTN_OK;
+}
+
+void dit_attn_destroy(dit_attn_ctx* ctx) {
+  if (!ctx) return;
+  DeviceGuard guard;
+  if (guard.enter(ctx->device) == hipSuccess) {
+    for (auto& p : ctx->plans)
+      if (p->dev_items) (void)hipFree(p->dev_items);
+    if (ctx->counter) (void)hipFree(ctx->counter);
+  }
+  (void)hipGetLastError();
+  delete ctx;
+}
+
+const char* dit_attn_last_error(const dit_attn_ctx* ctx) {
+  return ctx ? ctx->error.c_str() : g_create_error.c_str();
+}
+
+int64_t dit_attn_plan(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int32_t head_dim, int32_t* items,
+                      int64_t capacity_items, int32_t* block_m) {
+  std::string msg;
+  const int rc = check_shape_args(cu_seqlens, n_seqs, n_heads, head_dim, msg);
+  if (rc != DIT_ATTN_OK) return rc;
+  if (capacity_items > 0 && !items) return DIT_ATTN_ERR_NULL;
+  const int bm = dit::attn_fwd_block_m(head_dim);
+  if (block_m) *block_m = bm;
+  std::vector<dit::WorkItem> list;
+  try {
+    dit::plan_build(cu_seqlens, n_seqs, n_heads, bm, list);
+  } catch (...) {
+    return DIT_ATTN_ERR_CAPACITY;
+  }
+  const int64_t n = static_cast<int64_t>(list.size());
+  if (capacity_items > 0) {
+    if (capacity_items < n) return DIT_ATTN_ERR_CAPACITY;
+    if (n > 0) std::memcpy(items, list.data(), static_cast<size_t>(n) * sizeof(dit::WorkItem));
+  }
+  return n;
+}
+
+int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                        int32_t n_seqs, int32_t n_heads, int32_t head_dim, float scale, void* out, void* stream) {
+  if (!ctx) return DIT_ATTN_ERR_NULL;
+  ctx->error.clear();
+  std::string msg;
+  const int rc = check_shape_args(cu_seqlens, n_seqs, n_heads, head_dim, msg);
+  if (rc != DIT_ATTN_OK) return fail(ctx, rc, msg);
+  if (!std::isfinite(scale)) return fail(ctx, DIT_ATTN_ERR_SCALE, "scale must be finite");
+  const int64_t total = n_seqs > 0 ? cu_seqlens[n_seqs] : 0;
+  if (n_seqs == 0 || total == 0) return DIT_ATTN_OK;
+  if (!q || !k || !v || !out) return fail(ctx, DIT_ATTN_ERR_NULL, "q, k, v and out must be non-NULL");
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) |
+                         reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(out);
+  if (bits & 15u) return fail(ctx, DIT_ATTN_ERR_ALIGN, "q, k, v and out must be 16-byte aligned");
+
+  DeviceGuard guard;
+  hipError_t e = guard.enter(ctx->device);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  // Plan cache: the same pack comes back for every DiT block of every step.
+  CachedPlan* plan = nullptr;
+  const size_t cu_n = static_cast<size_t>(n_seqs) + 1;
+  for (auto& p : ctx->plans) {
+    if (p->n_heads == n_heads && p->head_dim == head_dim && p->cu.size() == cu_n &&
+        std::memcmp(p->cu.data(), cu_seqlens, cu_n * sizeof(int32_t)) == 0) {
+      plan = p.get();
+      break;
+    }
+  }
+  if (!plan) {
+    std::unique_ptr<CachedPlan> np;
+    try {
+      np.reset(new CachedPlan());
+      np->cu.assign(cu_seqlens, cu_seqlens + cu_n);
+      np->n_heads = n_heads;
+      np->head_dim = head_dim;
+      dit::plan_build(cu_seqlens, n_seqs, n_heads, dit::attn_fwd_block_m(head_dim), np->host_items);
+    } catch (...) {
+      return fail(ctx, DIT_ATTN_ERR_HIP, "out of host memory while building the work-list");
+    }
+    if (np->host_items.size() > kMaxItems) return fail(ctx, DIT_ATTN_ERR_CU_SEQLENS, "pack has too many work items");
+    const size_t bytes = np->host_items.size() * sizeof(dit::WorkItem);
+    e = hipMalloc(reinterpret_cast<void**>(&np->dev_items), bytes);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipMalloc(work-list)");
+    e = hipMemcpyAsync(np->dev_items, np->host_items.data(), bytes, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) {
+      (void)hipFree(np->dev_items);
+      return fail_hip(ctx, e, "hipMemcpyAsync(work-list)");
+    }
+    if (ctx->plans.size() >= kMaxCachedPlans) {
+      // Evict the least recently used plan.  hipFree waits for the device, so no kernel still reads it.
+      size_t victim = 0;
+      for (size_t i = 1; i < ctx->plans.size(); ++i)
+        if (ctx->plans[i]->last_use < ctx->plans[victim]->last_use) victim = i;
+      (void)hipFree(ctx->plans[victim]->dev_items);
+      ctx->plans.erase(ctx->plans.begin() + static_cast<std::ptrdiff_t>(victim));
+    }
+    plan = np.get();
+    ctx->plans.push_back(std::move(np));
+  }
+  plan->last_use = ++ctx->tick;
+
+  const uint32_t n_items = static_cast<uint32_t>(plan->host_items.size());
+  if (n_items == 0) return DIT_ATTN_OK;
+  const int64_t max_grid = static_cast<int64_t>(ctx->n_cus) * dit::attn_fwd_wgs_per_cu(head_dim);
+  const int grid = static_cast<int>(n_items < max_grid ? n_items : max_grid);
+
+  dit::AttnParams p;
+  p.q = q;
+  p.k = k;
+  p.v = v;
+  p.out = out;
+  p.items = plan->dev_items;
+  p.counter = ctx->counter;
+  p.counter_base = ctx->counter_value;
+  p.n_items = n_items;
+  p.n_heads = n_heads;
+  p.c_log2 = std::fabs(scale) * 1.44269504088896340736f;
+  p.negate = scale < 0.f ? 1 : 0;
+  e = dit::attn_fwd_launch(p, head_dim, grid, s);
+  if (e != hipSuccess) return fail_hip(ctx, e, "kernel launch");
+  // Every workgroup takes one value past the end of the list before it exits.
+  ctx->counter_value += n_items + static_cast<uint32_t>(grid);
+  return DIT_ATTN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,32 @@
+// Host-side work-list ("plan") for one packed denoising-step attention call.
+//
+// A batch handed to a GPU for one step mixes requests of very different length
+// (paper Section 4.3: image requests are batched, Section 3 / Table 3: a video
+// step has up to two orders of magnitude more tokens than an image step).  The
+// plan cuts every (sequence, head) into query tiles and orders the tiles so
+// that persistent workgroups, which take items in list order, finish together.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+namespace dit {
+
+// 16-byte record consumed by the kernel.
+struct WorkItem {
+  int32_t q_start;    // first global query row of the tile
+  int32_t kv_start;   // first global key row (start of the tile's sequence)
+  int32_t kv_len;     // keys in the sequence
+  int32_t rows_head;  // (q_rows << 16) | head, q_rows in 1..block_m
+};
+static_assert(sizeof(WorkItem) == 16, "WorkItem must be 16 bytes");
+
+// Validate cu_seqlens: returns 0 if ok (cu[0]==0, non-decreasing, n_seqs>=0), else non-zero.
+int plan_validate(const int32_t* cu_seqlens, int32_t n_seqs);
+
+// Build the ordered work-list.  Longest sequences first (their tiles cost the
+// most); inside a sequence, heads are the slow index and query tiles the fast
+// one, so workgroups running side by side stream the same K/V rows.
+void plan_build(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int32_t block_m,
+                std::vector<WorkItem>& items);
+
+}  // namespace dit

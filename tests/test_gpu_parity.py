@@ -1,0 +1,261 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same seeded inputs.
+
+Bar (from the benchmark definition): max-abs error <= 2e-2 and relative L2 error <= 1e-2
+(bf16 inputs, fp32 accumulation); which rows are written, and which keys feed them, bit-exact.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_04335_amd as da
+from dit_workloads import bf16_bits_to_f32, f32_to_bf16_bits, make_custom, make_workload, sample_rows
+from oracle import dit_attn_oracle as orc
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+from gpu_util import MAX_ABS_TOL, REL_L2_TOL, Runner, assert_parity, errors, to_bits, to_dev, widen  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def runner():
+    r = Runner()
+    yield r
+    r.close()
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ element-by-element on small packs
+
+SMALL = [
+    # (lens, H, D, seed)  -- several tiles (128-row query tiles, 64-key tiles) and ragged tails
+    ([300, 77, 129, 1, 0, 64, 200], 3, 128, 1),
+    ([1, 2, 3, 31, 32, 33, 63, 64, 65, 127, 128, 129], 2, 128, 2),
+    ([513], 5, 64, 3),
+    ([96, 640, 0, 17], 4, 64, 4),
+    ([1000], 1, 128, 5),
+    ([255, 257], 40, 128, 6),
+]
+
+
+@pytest.mark.parametrize("lens,H,D,seed", SMALL, ids=[f"case{i}" for i in range(len(SMALL))])
+def test_small_packs_full_oracle(runner, lens, H, D, seed):
+    _say(f"small pack lens={lens} H={H} D={D} seed={seed}")
+    w = make_custom(lens, H, D, seed)
+    got = runner.run(w)
+    ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    assert_parity(got, ref, f"lens={lens}")
+    # per sequence as well, so that one short sequence cannot hide behind a long one
+    cu = w.cu_seqlens
+    for i in range(len(lens)):
+        s, e = int(cu[i]), int(cu[i + 1])
+        if e > s:
+            assert_parity(got[s:e], ref[s:e], f"seq {i} of lens={lens}")
+
+
+def test_tiny_image_full_oracle(runner):
+    _say("config tiny_image, full oracle")
+    w = make_workload("tiny_image")
+    got = runner.run(w)
+    ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    max_abs, rel = assert_parity(got, ref, "tiny_image")
+    _say(f"tiny_image max_abs={max_abs:.3e} rel_l2={rel:.3e}")
+
+
+# ------------------------------------------------------------------ the four large configurations, sampled rows
+
+LARGE = [("t2i_batch", 600), ("t2v_single", 400), ("mixed_varlen", 700), ("sp_shard", 320)]
+
+
+@pytest.mark.parametrize("name,max_rows", LARGE, ids=[n for n, _ in LARGE])
+def test_full_size_configs_sampled_rows(runner, name, max_rows):
+    """Full-size call in the benchmark's launch configuration; the oracle checks a stratified row sample
+    (every sampled row uses all keys of its sequence, so each checked row is exact)."""
+    _say(f"config {name}: generating")
+    w = make_workload(name)
+    if os.environ.get("DIT_ORACLE_FULL") == "1":
+        max_rows = None
+    rows = sample_rows(w.cu_seqlens, seed=w.seed, block=64, max_rows=max_rows)
+    _say(f"config {name}: T={w.total_tokens} H={w.n_heads} rows checked={len(rows)}; running GPU")
+    got = runner.run(w)
+    _say(f"config {name}: running oracle on {len(rows)} rows")
+    ref = orc.attention_varlen_rows(w.q, w.k, w.v, w.cu_seqlens, w.scale, rows)
+    max_abs, rel = assert_parity(got[rows], ref, name)
+    _say(f"config {name}: max_abs={max_abs:.3e} rel_l2={rel:.3e} max|ref|={np.max(np.abs(ref)):.3e}")
+    # per sequence
+    cu = w.cu_seqlens
+    for i in range(len(cu) - 1):
+        sel = np.nonzero((rows >= cu[i]) & (rows < cu[i + 1]))[0]
+        if len(sel):
+            assert_parity(got[rows[sel]], ref[sel], f"{name} seq {i}")
+    # property that holds at any size: every output lies in the convex hull of its sequence's values
+    vf = bf16_bits_to_f32(w.v)
+    gf = bf16_bits_to_f32(got)
+    for i in range(len(cu) - 1):
+        s, e = int(cu[i]), int(cu[i + 1])
+        if e > s:
+            lo, hi = vf[s:e].min(axis=0), vf[s:e].max(axis=0)
+            assert np.all(gf[s:e] >= lo[None] - 1e-6) and np.all(gf[s:e] <= hi[None] + 1e-6)
+
+
+# ------------------------------------------------------------------ invariants, on the GPU
+
+def test_one_token_sequences_return_v_bits(runner):
+    w = make_custom([1, 130, 1, 1], 3, 128, seed=20)
+    got = runner.run(w)
+    for r in (0, 131, 132):
+        assert np.array_equal(got[r], w.v[r])
+
+
+def test_pack_isolation_bitwise(runner):
+    """A sequence's output bits do not depend on what it is packed with."""
+    w = make_custom([200, 333, 64], 2, 128, seed=21)
+    full = runner.run(w)
+    cu = w.cu_seqlens
+    for i in range(3):
+        s, e = int(cu[i]), int(cu[i + 1])
+        alone = make_custom([e - s], 2, 128, seed=0)
+        alone.q, alone.k, alone.v = w.q[s:e].copy(), w.k[s:e].copy(), w.v[s:e].copy()
+        assert np.array_equal(runner.run(alone), full[s:e]), f"sequence {i}"
+    # perturb the middle sequence: neighbours unchanged bit for bit
+    w2 = make_custom([200, 333, 64], 2, 128, seed=21)
+    w2.k[200:533] = f32_to_bf16_bits(bf16_bits_to_f32(w2.k[200:533]) + 1.0)
+    w2.v[200:533] = f32_to_bf16_bits(bf16_bits_to_f32(w2.v[200:533]) * 2.0)
+    pert = runner.run(w2)
+    assert np.array_equal(pert[:200], full[:200]) and np.array_equal(pert[533:], full[533:])
+    assert not np.array_equal(pert[200:533], full[200:533])
+
+
+def test_head_subset_equals_heads_of_wider_run(runner):
+    """The head-split shard view: running heads [10, 20) alone equals those heads of a 40-head run."""
+    w = make_custom([700], 40, 128, seed=22)
+    full = runner.run(w)
+    sub = make_custom([700], 10, 128, seed=0)
+    sub.q, sub.k, sub.v = (np.ascontiguousarray(x[:, 10:20]) for x in (w.q, w.k, w.v))
+    assert np.array_equal(runner.run(sub), full[:, 10:20])
+
+
+def test_scale_zero_and_negative_scale(runner):
+    w = make_custom([150, 70], 2, 64, seed=23)
+    got0 = widen(runner.run(w, scale=0.0))
+    vf = widen(w.v)
+    for s, e in ((0, 150), (150, 220)):
+        mean = vf[s:e].mean(axis=0)
+        assert np.max(np.abs(got0[s:e] - mean[None])) <= 4e-3  # bf16 rounding of the output
+    neg = runner.run(w, scale=-0.2)
+    ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, -0.2)
+    assert_parity(neg, ref, "negative scale")
+
+
+def test_identical_keys_give_mean_of_v(runner):
+    w = make_custom([257], 2, 128, seed=24)
+    w.k[:] = w.k[0:1]
+    got = widen(runner.run(w))
+    mean = widen(w.v).mean(axis=0)
+    assert np.max(np.abs(got - mean[None])) <= 4e-3
+
+
+def test_key_permutation_invariance(runner):
+    w = make_custom([389], 2, 128, seed=25)
+    base = widen(runner.run(w))
+    perm = np.random.Generator(np.random.PCG64(7)).permutation(389)
+    w.k, w.v = np.ascontiguousarray(w.k[perm]), np.ascontiguousarray(w.v[perm])
+    got = widen(runner.run(w))
+    max_abs, rel = errors(got, base)
+    assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+
+
+def test_peaky_softmax_large_logits(runner):
+    """Logit standard deviation ~16: exercises the running-maximum path."""
+    w = make_custom([300], 2, 128, seed=26, scale=16.0 / np.sqrt(128.0))
+    got = runner.run(w)
+    ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    assert_parity(got, ref, "peaky")
+
+
+def test_increasing_logits_force_rescaling(runner):
+    """Keys ordered so that the row maximum grows tile after tile."""
+    w = make_custom([640], 1, 128, seed=27, scale=1.0)
+    qf = np.ones((640, 1, 128), dtype=np.float32) * 0.25
+    kf = np.zeros((640, 1, 128), dtype=np.float32)
+    kf[:, 0, :] = (np.arange(640, dtype=np.float32) / 640.0)[:, None]  # logit j = 32 * j / 640
+    w.q, w.k = f32_to_bf16_bits(qf), f32_to_bf16_bits(kf)
+    got = runner.run(w)
+    ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    assert_parity(got, ref, "increasing logits")
+
+
+# ------------------------------------------------------------------ call mechanics
+
+def test_deterministic_and_plan_cache(runner):
+    a = make_custom([300, 200], 2, 128, seed=30)
+    b = make_custom([123], 2, 128, seed=31)
+    ra1 = runner.run(a)
+    rb1 = runner.run(b)
+    ra2 = runner.run(a)
+    rb2 = runner.run(b)
+    assert np.array_equal(ra1, ra2) and np.array_equal(rb1, rb2)
+
+
+def test_many_packs_evict_cached_plans(runner):
+    ref = None
+    for i in range(40):  # more distinct packs than the cache holds
+        w = make_custom([64 + i, 10], 1, 64, seed=32)
+        got = runner.run(w)
+        if i == 0:
+            ref = got
+    w = make_custom([64, 10], 1, 64, seed=32)
+    assert np.array_equal(runner.run(w), ref)
+
+
+def test_non_default_stream(runner):
+    w = make_custom([400], 2, 128, seed=33)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        out = runner.run_dev(q, k, v, w.cu_seqlens, 2, 128, w.scale, stream=st.cuda_stream)
+    ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    assert_parity(to_bits(out), ref, "stream")
+
+
+def test_empty_inputs_launch_nothing(runner):
+    da.dit_attn_varlen_fwd(runner.ctx, 0, 0, 0, np.array([0], dtype=np.int32), 2, 128, 1.0, 0, None)
+    da.dit_attn_varlen_fwd(runner.ctx, 0, 0, 0, np.array([0, 0, 0], dtype=np.int32), 2, 128, 1.0, 0, None)
+
+
+def test_argument_errors_leave_out_untouched(runner):
+    w = make_custom([100], 2, 128, seed=34)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    out = torch.full((100, 2, 128), 0x7FC1, dtype=torch.int16, device="cuda")
+    cu = w.cu_seqlens
+
+    def expect(code, **kw):
+        args = dict(q=q, k=k, v=v, cu=cu, H=2, D=128, scale=1.0, out=out)
+        args.update(kw)
+        with pytest.raises(da.DitAttnError) as ei:
+            da.dit_attn_varlen_fwd(runner.ctx, args["q"], args["k"], args["v"], args["cu"], args["H"], args["D"],
+                                   args["scale"], args["out"], None)
+        assert ei.value.code == code, (code, ei.value)
+
+    expect(-2, D=96)
+    expect(-6, H=0)
+    expect(-3, cu=np.array([1, 100], dtype=np.int32))
+    expect(-3, cu=np.array([0, 100, 50], dtype=np.int32))
+    expect(-5, scale=float("nan"))
+    expect(-5, scale=float("inf"))
+    expect(-1, q=0)
+    expect(-1, out=0)
+    expect(-7, k=k.data_ptr() + 2)
+    torch.cuda.synchronize()
+    assert bool((out == 0x7FC1).all())
+    assert "aligned" in da.dit_attn_last_error(runner.ctx)
+    # and the context still works afterwards
+    got = runner.run(w)
+    assert_parity(got, orc.attention_varlen(w.q, w.k, w.v, cu, w.scale), "after errors")

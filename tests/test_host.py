@@ -1,0 +1,103 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header declares,
+and the work-list covers every (sequence, head, query row) exactly once."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2604_04335_amd as da
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dit_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dit_attn_[a-z_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = da.load_library()
+    names = _declared_symbols()
+    assert {"dit_attn_create", "dit_attn_varlen_fwd", "dit_attn_destroy", "dit_attn_last_error",
+            "dit_attn_plan", "dit_attn_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert "gfx950" in da.dit_attn_version()
+
+
+def test_no_cpu_fallback_when_no_device():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(da.DitAttnError) as ei:
+        da.dit_attn_create(0)
+    assert ei.value.code == -4
+
+
+def _check_plan(lens, H, D):
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    items, bm = da.dit_attn_plan(cu, H, D)
+    assert bm in (64, 128, 256)
+    T = int(cu[-1])
+    cover = np.zeros((T, H), dtype=np.int32)
+    seq_of = np.repeat(np.arange(len(lens)), lens)
+    for q_start, kv_start, kv_len, rh in items.tolist():
+        rows, head = rh >> 16, rh & 0xFFFF
+        assert 1 <= rows <= bm and 0 <= head < H
+        s = seq_of[q_start]
+        assert kv_start == cu[s] and kv_len == cu[s + 1] - cu[s]
+        assert q_start + rows <= cu[s + 1]
+        # tiles start at the sequence start, in steps of block_m
+        assert (q_start - kv_start) % bm == 0
+        cover[q_start:q_start + rows, head] += 1
+    assert np.all(cover == 1)
+    # longest first
+    kv = items[:, 2]
+    assert np.all(np.diff(kv) <= 0)
+    return items, bm
+
+
+@pytest.mark.parametrize("lens,H,D", [
+    ([1024], 8, 64),
+    ([4352] * 4, 24, 128),
+    ([5, 0, 300, 1, 129, 128, 127], 3, 128),
+    ([0, 0], 2, 64),
+    ([4352, 1280, 20506, 4352, 1280], 2, 128),
+])
+def test_plan_covers_every_row_once(lens, H, D):
+    items, bm = _check_plan(lens, H, D)
+    expect = sum(-(-l // bm) for l in lens) * H
+    assert len(items) == expect
+
+
+def test_plan_is_independent_of_packing():
+    # a sequence's tiles (relative to its start) do not depend on its neighbours
+    a, bm = da.dit_attn_plan(np.array([0, 300], dtype=np.int32), 2, 128)
+    b, _ = da.dit_attn_plan(np.array([0, 77, 377], dtype=np.int32), 2, 128)
+    b = b[b[:, 2] == 300]
+    assert np.array_equal(a[:, 0] - a[:, 1], b[:, 0] - b[:, 1]) and np.array_equal(a[:, 3], b[:, 3])
+
+
+def test_plan_rejects_bad_arguments():
+    lib = da.load_library()
+    i32p = ctypes.POINTER(ctypes.c_int32)
+
+    def call(cu, n_seqs, H, D):
+        arr = np.asarray(cu, dtype=np.int32)
+        return lib.dit_attn_plan(arr.ctypes.data_as(i32p), n_seqs, H, D, None, 0, None)
+
+    assert call([0, 4], 1, 2, 128) == 2 * 1
+    assert call([1, 4], 1, 2, 128) == -3      # does not start at 0
+    assert call([0, 4, 3], 2, 2, 128) == -3   # decreasing
+    assert call([0, 4], -1, 2, 128) == -3
+    assert call([0, 4], 1, 2, 96) == -2
+    assert call([0, 4], 1, 0, 128) == -6
+    assert call([0, 4], 1, 70000, 128) == -6
+    assert lib.dit_attn_plan(None, 1, 2, 128, None, 0, None) == -1
+    # capacity too small
+    buf = np.zeros(4, dtype=np.int32)
+    arr = np.array([0, 1000], dtype=np.int32)
+    assert lib.dit_attn_plan(arr.ctypes.data_as(i32p), 1, 2, 128, buf.ctypes.data_as(i32p), 1, None) == -8
