@@ -20,12 +20,14 @@ struct CachedPlan {
   std::vector<int32_t> cu;  // key: cu_seqlens contents
   int32_t n_heads = 0;
   int32_t head_dim = 0;
+  dit::AttnKernel kernel = dit::AttnKernel::kIndependent128;
   std::vector<dit::WorkItem> host_items;  // kept alive: source of the stream-ordered upload
   dit::WorkItem* dev_items = nullptr;
   uint64_t last_use = 0;
 };
 
 constexpr size_t kMaxCachedPlans = 32;
+constexpr int kMi355xComputeUnits = 256;  // what dit_attn_plan assumes when it has no device to ask
 constexpr size_t kMaxItems = size_t(1) << 30;
 
 thread_local std::string g_create_error;
@@ -167,7 +169,8 @@ int64_t dit_attn_plan(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads
   const int rc = check_shape_args(cu_seqlens, n_seqs, n_heads, head_dim, msg);
   if (rc != DIT_ATTN_OK) return rc;
   if (capacity_items > 0 && !items) return DIT_ATTN_ERR_NULL;
-  const int bm = dit::attn_fwd_block_m(head_dim);
+  const dit::AttnKernel kernel = dit::attn_fwd_select(cu_seqlens, n_seqs, n_heads, kMi355xComputeUnits);
+  const int bm = dit::attn_fwd_block_m(kernel);
   if (block_m) *block_m = bm;
   std::vector<dit::WorkItem> list;
   try {
@@ -220,7 +223,8 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
       np->cu.assign(cu_seqlens, cu_seqlens + cu_n);
       np->n_heads = n_heads;
       np->head_dim = head_dim;
-      dit::plan_build(cu_seqlens, n_seqs, n_heads, dit::attn_fwd_block_m(head_dim), np->host_items);
+      np->kernel = dit::attn_fwd_select(cu_seqlens, n_seqs, n_heads, ctx->n_cus);
+      dit::plan_build(cu_seqlens, n_seqs, n_heads, dit::attn_fwd_block_m(np->kernel), np->host_items);
     } catch (...) {
       return fail(ctx, DIT_ATTN_ERR_HIP, "out of host memory while building the work-list");
     }
@@ -248,7 +252,7 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
 
   const uint32_t n_items = static_cast<uint32_t>(plan->host_items.size());
   if (n_items == 0) return DIT_ATTN_OK;
-  const int64_t max_grid = static_cast<int64_t>(ctx->n_cus) * dit::attn_fwd_wgs_per_cu(head_dim);
+  const int64_t max_grid = static_cast<int64_t>(ctx->n_cus) * dit::attn_fwd_wgs_per_cu(plan->kernel);
   const int grid = static_cast<int>(n_items < max_grid ? n_items : max_grid);
 
   dit::AttnParams p;
@@ -263,7 +267,7 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
   p.n_heads = n_heads;
   p.c_log2 = std::fabs(scale) * 1.44269504088896340736f;
   p.negate = scale < 0.f ? 1 : 0;
-  e = dit::attn_fwd_launch(p, head_dim, grid, s);
+  e = dit::attn_fwd_launch(p, plan->kernel, head_dim, grid, s);
   if (e != hipSuccess) return fail_hip(ctx, e, "kernel launch");
   // Every workgroup takes one value past the end of the list before it exits.
   ctx->counter_value += n_items + static_cast<uint32_t>(grid);

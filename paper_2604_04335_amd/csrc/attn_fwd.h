@@ -21,12 +21,21 @@ struct AttnParams {
   int32_t negate;           // 1 when scale < 0: the sign of Q is flipped on load
 };
 
-// Query rows per work item and resident workgroups per compute unit for a head dimension.
-int attn_fwd_block_m(int head_dim);
-int attn_fwd_wgs_per_cu(int head_dim);
+// Two kernels share the tile code.
+//   kIndependent128: 4 wavefronts, 128 query rows per item, two unsynchronised workgroups per compute unit.
+//   kPingPong256:    8 wavefronts, 256 query rows per item, one workgroup per compute unit whose two wavefront
+//                    groups alternate between the matrix and the vector phase of consecutive tiles.
+enum class AttnKernel : int { kIndependent128 = 0, kPingPong256 = 1 };
+
+// Which kernel a pack runs on a device with n_cus compute units (a pure function of the pack).
+AttnKernel attn_fwd_select(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int n_cus);
+
+// Query rows per work item and resident workgroups per compute unit of a kernel.
+int attn_fwd_block_m(AttnKernel kernel);
+int attn_fwd_wgs_per_cu(AttnKernel kernel);
 
 // Enqueue the forward kernel with `grid` persistent workgroups.  Every workgroup takes exactly one
 // counter value at or beyond n_items, so the counter ends at counter_base + n_items + grid.
-hipError_t attn_fwd_launch(const AttnParams& p, int head_dim, int grid, hipStream_t stream);
+hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim, int grid, hipStream_t stream);
 
 }  // namespace dit

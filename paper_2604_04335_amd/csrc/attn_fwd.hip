@@ -4,11 +4,10 @@
 // keys of r's own sequence (paper Sections 4.3 and 5 give the batch; the math is
 // plain softmax attention).  bf16 in, fp32 scores/state/accumulators, bf16 out.
 //
-// Mapping.  A persistent workgroup of NWAVES wavefronts takes (sequence, head,
-// query tile) items from a list through one atomic counter.  Each wavefront owns
-// 32 query rows.  K and V tiles of BN keys are copied HBM -> LDS by direct
-// (register-free) loads, double buffered, one barrier per tile.  Both
-// contractions run on the 32x32x16 bf16 MFMA in *transposed* form:
+// Mapping.  A persistent workgroup takes (sequence, head, query tile) items from
+// a list through one atomic counter.  Each wavefront owns 32 query rows.  K and V
+// tiles of BN keys are copied HBM -> LDS by direct (register-free) loads, double
+// buffered.  Both contractions run on the 32x32x16 bf16 MFMA in *transposed* form:
 //     S^T[key, query] = K[key, :] . Q[query, :]        A = K (from LDS), B = Q (registers)
 //     O^T[d,   query] += V^T[d, key] . P^T[key, query] A = V^T (LDS transpose read), B = P (registers)
 // In the MFMA result layout a lane holds one query column and 16 key rows, so the
@@ -24,6 +23,11 @@
 // pass (K) and the 4 rows x 64 B a transpose read touches per pass (V) fall in
 // distinct banks.  The swizzle is applied by choosing which global chunk a lane
 // fetches, so it costs nothing.
+//
+// O^T and the running sum are rescaled only in tiles where the maximum of some row of the wavefront
+// grows.  The reference maximum is always the true running maximum, so the largest probability of a
+// row is exactly 1 and is not perturbed by the bf16 rounding of P (a row dominated by one key then
+// returns that key's V row exactly; a stale reference would cost up to 2^-9 relative there).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -44,10 +48,10 @@ typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 typedef __attribute__((address_space(1))) const void gptr_void;
 
-// O^T and the running sum are rescaled only in tiles where the maximum of some row of the wavefront
-// grows.  The reference maximum is always the true running maximum, so the largest probability of a
-// row is exactly 1 and is not perturbed by the bf16 rounding of P (a row dominated by one key then
-// returns that key's V row exactly; a stale reference would cost up to 2^-9 relative there).
+// Operand reads of an MFMA stream run this many MFMAs ahead of their use.
+constexpr int kPrefetch = 4;
+// Full scheduling fence: the compiler's instruction scheduler moves nothing across it.
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 template <int D_, int NWAVES_, int BN_>
 struct Tile {
@@ -65,6 +69,12 @@ struct Tile {
   static constexpr int NKB = BN / 32;              // 32-key blocks per tile
   static constexpr int NKS = D / 16;               // k-steps of the first contraction
   static constexpr int NDB = D / 32;               // 32-wide d blocks of the output
+  static constexpr int NQK = NKB * NKS;            // MFMAs of S^T = K Q^T per tile
+  static constexpr int NPV = NKB * 2 * NDB;        // MFMAs of O^T += V^T P^T per tile
+  // LDS: [K0][K1][V0][V1][two item slots]
+  static constexpr int K_OFF = 0;
+  static constexpr int V_OFF = 2 * TILE_B;
+  static constexpr int ITEM_OFF = 4 * TILE_B;
   static constexpr int LDS_BYTES = 4 * TILE_B + 16;
   static_assert(GROUP % 16 == 0 && BN % GROUP == 0, "load rounds must keep row%16 fixed per lane");
   static_assert(D == 64 || D == 128, "head dimension");
@@ -82,45 +92,184 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
-// Issue the direct HBM -> LDS loads of one K tile and one V tile (this wave's share).
-// koff / voff: per-lane byte offset of (row lrow, swizzled chunk) relative to a GROUP-row block.
-template <class T, bool TAIL>
-__device__ __forceinline__ void tile_load(const char* __restrict__ kbase, const char* __restrict__ vbase,
-                                          int64_t row_stride_b, int key0, int kv_len, int lrow, int kcol, int vcol,
-                                          lds_char* kdst, lds_char* vdst, int wave) {
+// Per-lane constants of a kernel instance.
+template <class T>
+struct Lane {
+  int lane, wave, l32, hh;
+  int lrow;               // row of this lane inside a GROUP-row load round
+  int kcol, vcol;         // byte column (swizzled chunk) this lane fetches for K / V
+  uint32_t kvoff, vvoff;  // lrow * row_stride + column, the 32-bit per-lane part of a load address
+
+  __device__ __forceinline__ void init(int tid, int64_t row_stride_b) {
+    lane = tid & 63;
+    wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    l32 = lane & 31;
+    hh = lane >> 5;
+    lrow = wave * T::RPI + lane / T::CPR;
+    kcol = ((lane % T::CPR) ^ T::swz_k(lrow)) * 16;
+    vcol = ((lane % T::CPR) ^ T::swz_v(lrow)) * 16;
+    kvoff = (uint32_t)lrow * (uint32_t)row_stride_b + (uint32_t)kcol;
+    vvoff = (uint32_t)lrow * (uint32_t)row_stride_b + (uint32_t)vcol;
+  }
+
+  // Operand addresses in the K / V buffers of parity 0 (recomputed per item: cheaper than keeping a second copy live).
+  //   ka[ks]: K operand chunk of k-step ks, 32-key block 0.   va[db]: V transpose read of d-block db, 16-key block 0.
+  // V^T operand: lane (d = 32*db + lane%32, half hh) needs keys {k0 .. k0+3} and {k0+8 .. k0+11},
+  // k0 = 32*kb + 16*u + 4*hh.  A transpose read returns, to lane i of a 16-lane group, element i%4 of
+  // the 8 bytes addressed by lanes i/4 + {0,4,8,12} of the group; so the lane addresses row k0 + (i16/4),
+  // columns 16*b + 4*(i16%4) .. +3 of the d-block and receives column 16*b + i16 of rows k0 .. k0+3.
+  __device__ __forceinline__ void operand_addrs(uint32_t lds_base, int (&ka)[T::NKS], int (&va)[T::NDB]) const {
+    const int i16 = lane & 15;
+    const int b = (lane >> 4) & 1;
 #pragma unroll
-  for (int i = 0; i < T::LPT; ++i) {
-    int row = key0 + i * T::GROUP + lrow;
-    if (TAIL) row = row < kv_len ? row : kv_len - 1;  // rows past the end re-read the last key; they are masked
-    const int64_t roff = (int64_t)row * row_stride_b;
-    lds_char* kd = kdst + (i * T::NWAVES + wave) * 1024;
-    lds_char* vd = vdst + (i * T::NWAVES + wave) * 1024;
-    __builtin_amdgcn_global_load_lds((gptr_void*)(kbase + roff + kcol), (__attribute__((address_space(3))) void*)kd, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((gptr_void*)(vbase + roff + vcol), (__attribute__((address_space(3))) void*)vd, 16, 0, 0);
+    for (int ks = 0; ks < T::NKS; ++ks) ka[ks] = (int)lds_base + T::K_OFF + l32 * T::ROW_B + (((2 * ks + hh) ^ T::swz_k(l32)) * 16);
+    const int row = 4 * hh + (i16 >> 2);
+#pragma unroll
+    for (int db = 0; db < T::NDB; ++db) {
+      const int chunk = 4 * db + 2 * b + ((i16 & 3) >> 1);
+      va[db] = (int)lds_base + T::V_OFF + row * T::ROW_B + ((chunk ^ T::swz_v(row)) * 16) + 8 * (i16 & 1);
+    }
+  }
+};
+
+// Direct HBM -> LDS load of this wave's share of one K or V tile into the tile buffer at LDS byte offset dst_off.
+// base (start of the sequence's rows for this head), row_stride_b, key0 and kv_len are wave-uniform.  The address of a
+// lane is  scalar tile base + 32-bit lane offset;  in the last tile of a sequence rows past the end re-read the last
+// key (their scores are masked, and a finite V row times a zero probability adds nothing).
+// One direct-load instruction: 64 lanes x 16 bytes from (sbase + voff[lane]) to LDS bytes [lds_addr, lds_addr + 1024).
+// Written as inline assembly so that the compiler does not track it: it would otherwise make LDS reads that it
+// cannot prove disjoint wait for every outstanding direct load.  Completion is awaited explicitly (wait_loads).
+__device__ __forceinline__ void lds_dma_16(const char* sbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(sbase)
+               : "memory");
+}
+
+template <class T>
+__device__ __forceinline__ void tile_load_one(const char* base, int64_t row_stride_b, int key0, int kv_len, int lrow,
+                                              int col, uint32_t voff, lds_char* smem, int dst_off, int wave) {
+  const char* tbase = base + (int64_t)key0 * row_stride_b;  // scalar
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem + (uint32_t)dst_off + (uint32_t)wave * 1024u;
+  if (key0 + T::BN <= kv_len) {
+#pragma unroll
+    for (int i = 0; i < T::LPT; ++i) {
+      const char* sbase = tbase + (int64_t)(i * T::GROUP) * row_stride_b;  // scalar
+      lds_dma_16(sbase, voff, lds0 + i * T::NWAVES * 1024);
+    }
+  } else {
+    const int last = kv_len - 1 - key0;  // >= 0
+#pragma unroll
+    for (int i = 0; i < T::LPT; ++i) {
+      int row = i * T::GROUP + lrow;
+      row = row < last ? row : last;
+      const uint32_t off = (uint32_t)row * (uint32_t)row_stride_b + (uint32_t)col;
+      lds_dma_16(tbase, off, lds0 + i * T::NWAVES * 1024);
+    }
   }
 }
 
-// One K/V tile: S^T = K Q^T, online softmax, O^T += V^T P^T.
-// kaddr[ks]: per-lane LDS byte offset of the K operand chunk of k-step ks inside a 32-key block.
-// vaddr[db]: per-lane LDS byte offset of the V transpose read of d-block db inside a 16-key block.
-template <class T, bool TAIL>
-__device__ __forceinline__ void tile_compute(lds_char* kbuf, lds_char* vbuf, int hh, int keys_left, float c,
-                                             const int (&kaddr)[T::NKS], const int (&vaddr)[T::NDB],
-                                             const bf16x8 (&qf)[T::NKS], f32x16 (&o)[T::NDB], float& m_ref,
-                                             float& l_run) {
-  f32x16 s[T::NKB];
-#pragma unroll
-  for (int kb = 0; kb < T::NKB; ++kb) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < T::NKS; ++ks) {
-      const bf16x8 a = *(lds_bf16x8*)(kbuf + kaddr[ks] + kb * 32 * T::ROW_B);
-      s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
-    }
+template <int V>
+struct IC {
+  static constexpr int value = V;
+};
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(IC<I>{});
+    static_for<I + 1, N>(f);
   }
+}
 
-  // key index inside the tile of element i of block kb: 32*kb + 8*(i/4) + 4*hh + (i%4)
+// The MFMA stream of one tile step: optionally O^T += V^T P^T (V tile addressed by va), then optionally
+// S^T = K Q^T (K tile addressed by ka).  Operand reads run PD MFMAs ahead of their use, through a ring of PD
+// operand registers.
+template <class T, bool DO_PV, bool DO_QK, int PD>
+__device__ __forceinline__ void mfma_stream(lds_char* smem, const int (&va)[T::NDB], const int (&ka)[T::NKS],
+                                            const uint32_t (&pb)[T::NKB][8], const bf16x8 (&qf)[T::NKS],
+                                            f32x16 (&o)[T::NDB], f32x16 (&s)[T::NKB]) {
+  constexpr int NPV = DO_PV ? T::NPV : 0;
+  constexpr int NQK = DO_QK ? T::NQK : 0;
+  constexpr int N = NPV + NQK;
+  bf16x8 frag[PD];
+  int va_[T::NDB], ka_[T::NKS];
+#pragma unroll
+  for (int i = 0; i < T::NDB; ++i) va_[i] = va[i];
+#pragma unroll
+  for (int i = 0; i < T::NKS; ++i) ka_[i] = ka[i];
+
+  auto load_step = [&](auto jc) {
+    constexpr int J = decltype(jc)::value;
+    if constexpr (J < NPV) {  // PV step J: kb = J / (2*NDB), u = (J / NDB) % 2, db = J % NDB
+      constexpr int kb = J / (2 * T::NDB), u = (J / T::NDB) % 2, db = J % T::NDB;
+      lds_char* p0 = (lds_char*)(uintptr_t)(uint32_t)(va_[db] + (32 * kb + 16 * u) * T::ROW_B);
+      const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0));
+      const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * T::ROW_B));
+      frag[J % PD] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    } else {  // QK step: ks = q / NKB, kb = q % NKB (kb fastest: consecutive MFMAs use different accumulators)
+      constexpr int q = J - NPV, ks = q / T::NKB, kb = q % T::NKB;
+      frag[J % PD] = *(lds_bf16x8*)(uintptr_t)(uint32_t)(ka_[ks] + kb * 32 * T::ROW_B);
+    }
+  };
+  auto mfma_step = [&](auto jc) {
+    constexpr int J = decltype(jc)::value;
+    if constexpr (J < NPV) {
+      constexpr int kb = J / (2 * T::NDB), u = (J / T::NDB) % 2, db = J % T::NDB;
+      u32x4 pw = {pb[kb][4 * u], pb[kb][4 * u + 1], pb[kb][4 * u + 2], pb[kb][4 * u + 3]};
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], __builtin_bit_cast(bf16x8, pw), o[db], 0, 0, 0);
+    } else {
+      constexpr int q = J - NPV, ks = q / T::NKB, kb = q % T::NKB;
+      if constexpr (ks == 0) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], qf[ks], zero, 0, 0, 0);
+      } else {
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], qf[ks], s[kb], 0, 0, 0);
+      }
+    }
+  };
+
+  // Order.  The compiler is free to hoist LDS reads far above their MFMAs (it would then hold every operand of the
+  // stream in registers at once) and to reorder the two contractions.  An empty asm statement after each MFMA takes
+  // the accumulator just written as input and passes the address register of the next read through: the read cannot
+  // be issued before that MFMA, and volatile asm statements keep their order.  It emits no instruction.
+  auto tie = [&](auto jc) {
+    (void)s;
+    (void)o;
+    constexpr int J = decltype(jc)::value;   // MFMA just issued
+    constexpr int R = J + PD;                // read to issue next
+    if constexpr (R < N) {
+      if constexpr (J < NPV) {
+        constexpr int dbj = J % T::NDB;
+        if constexpr (R < NPV) {
+          asm volatile("" : "+v"(va_[R % T::NDB]) : "v"(o[dbj]));
+        } else {
+          asm volatile("" : "+v"(ka_[(R - NPV) / T::NKB]) : "v"(o[dbj]));
+        }
+      } else {
+        constexpr int kbj = (J - NPV) % T::NKB;
+        asm volatile("" : "+v"(ka_[(R - NPV) / T::NKB]) : "v"(s[kbj]));
+      }
+    }
+  };
+  SCHED_FENCE();
+  static_for<0, (PD < N ? PD : N)>([&](auto jc) { load_step(jc); });
+  SCHED_FENCE();
+  static_for<0, N>([&](auto jc) {
+    constexpr int J = decltype(jc)::value;
+    mfma_step(jc);
+    tie(jc);
+    if constexpr (J + PD < N) load_step(IC<J + PD>{});
+    SCHED_FENCE();  // and the scheduler may not sink that read towards its use either
+  });
+  SCHED_FENCE();
+}
+
+// Online softmax of one tile: scores s -> bf16 probabilities pb (B-operand order), running max / sum, lazy rescale.
+// Element i of block kb is key 32*kb + 8*(i/4) + 4*hh + (i%4) of the tile, for query lane%32.
+template <class T, bool TAIL>
+__device__ __forceinline__ void tile_softmax(f32x16 (&s)[T::NKB], int hh, int keys_left, float c,
+                                             uint32_t (&pb)[T::NKB][8], f32x16 (&o)[T::NDB], float& m_ref,
+                                             float& l_run) {
   if (TAIL) {
 #pragma unroll
     for (int kb = 0; kb < T::NKB; ++kb)
@@ -152,114 +301,154 @@ __device__ __forceinline__ void tile_compute(lds_char* kbuf, lds_char* vbuf, int
   }
   const float mc = m_ref * c;
 
+  // Eight scores at a time, with a scheduling fence after each group: the probabilities are packed to bf16 and
+  // their fp32 values die before the next group starts, which keeps the register peak of this phase low.
   float lsum = 0.f;
-  uint32_t pb[T::NKB][8];
 #pragma unroll
   for (int kb = 0; kb < T::NKB; ++kb) {
 #pragma unroll
-    for (int i = 0; i < 16; i += 2) {
-      float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -mc));
-      float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i + 1], c, -mc));
-      if (TAIL) {
-        const int key = 32 * kb + 8 * (i >> 2) + 4 * hh + (i & 3);
-        if (key >= keys_left) p0 = 0.f;
-        if (key + 1 >= keys_left) p1 = 0.f;
+    for (int g = 0; g < 2; ++g) {
+#pragma unroll
+      for (int i = 8 * g; i < 8 * g + 8; i += 2) {
+        float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -mc));
+        float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i + 1], c, -mc));
+        if (TAIL) {
+          const int key = 32 * kb + 8 * (i >> 2) + 4 * hh + (i & 3);
+          if (key >= keys_left) p0 = 0.f;
+          if (key + 1 >= keys_left) p1 = 0.f;
+        }
+        lsum += p0 + p1;
+        pb[kb][i >> 1] = pack_bf16x2(p0, p1);
       }
-      lsum += p0 + p1;
-      pb[kb][i >> 1] = pack_bf16x2(p0, p1);
+      SCHED_FENCE();
     }
   }
   l_run += lsum;
+}
 
-  // V^T operand: lane (d = 32*db + lane%32, half hh) needs keys {k0 .. k0+3} and {k0+8 .. k0+11},
-  // k0 = 32*kb + 16*u + 4*hh.  A transpose read returns, to lane i of a 16-lane group, element i%4 of
-  // the 8 bytes addressed by lanes i/4 + {0,4,8,12} of the group; so the lane addresses row k0 + (i16/4),
-  // columns 16*b + 4*(i16%4) .. +3 of the d-block and receives column 16*b + i16 of rows k0 .. k0+3.
+// All LDS accesses of this wave are complete, then workgroup barrier.  The "memory" clobber keeps the
+// compiler from moving LDS reads or direct loads across it.
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Work item fields, wave-uniform.
+struct ItemU {
+  int q_start, kv_start, kv_len, head, q_rows;
+};
+__device__ __forceinline__ ItemU fetch_item(const WorkItem* items, uint32_t idx) {
+  const WorkItem it = items[idx];
+  ItemU u;
+  u.q_start = __builtin_amdgcn_readfirstlane(it.q_start);
+  u.kv_start = __builtin_amdgcn_readfirstlane(it.kv_start);
+  u.kv_len = __builtin_amdgcn_readfirstlane(it.kv_len);
+  const int rh = __builtin_amdgcn_readfirstlane(it.rows_head);
+  u.head = rh & 0xFFFF;
+  u.q_rows = (rh >> 16) & 0xFFFF;
+  return u;
+}
+
+// Q fragments (B operand of S^T = K Q^T): lane holds query row l32 of its wave, d = 16*ks + 8*hh .. +7.
+template <class T>
+__device__ __forceinline__ void load_q(const AttnParams& p, const Lane<T>& L, const ItemU& it, int64_t row_stride_b,
+                                       int64_t head_off, int qrow, bf16x8 (&qf)[T::NKS]) {
+  const char* qptr = static_cast<const char*>(p.q) + (int64_t)(it.q_start + qrow) * row_stride_b + head_off + L.hh * 16;
 #pragma unroll
-  for (int kb = 0; kb < T::NKB; ++kb) {
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      u32x4 pw = {pb[kb][4 * u], pb[kb][4 * u + 1], pb[kb][4 * u + 2], pb[kb][4 * u + 3]};
-      const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-      for (int db = 0; db < T::NDB; ++db) {
-        lds_char* p0 = vbuf + vaddr[db] + (32 * kb + 16 * u) * T::ROW_B;
-        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0));
-        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * T::ROW_B));
-        const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pfrag, o[db], 0, 0, 0);
-      }
-    }
+  for (int ks = 0; ks < T::NKS; ++ks) {
+    u32x4 w = *reinterpret_cast<const u32x4*>(qptr + ks * 32);
+    if (p.negate) w ^= u32x4{0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
+    qf[ks] = __builtin_bit_cast(bf16x8, w);
   }
 }
 
+// Epilogue: O^T / l -> bf16 -> out.  Lane holds d = 32*db + 8*g + 4*hh + j (i = 4*g + j) of query l32.
+template <class T>
+__device__ __forceinline__ void store_out(const AttnParams& p, const Lane<T>& L, const ItemU& it, int64_t row_stride_b,
+                                          int64_t head_off, int qrow, bool row_valid, const f32x16 (&o)[T::NDB],
+                                          float l_run) {
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (row_valid) {
+    const float inv = 1.0f / l_tot;
+    char* optr = static_cast<char*>(p.out) + (int64_t)(it.q_start + qrow) * row_stride_b + head_off + L.hh * 8;
+#pragma unroll
+    for (int db = 0; db < T::NDB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 w;
+        w[0] = pack_bf16x2(o[db][4 * g + 0] * inv, o[db][4 * g + 1] * inv);
+        w[1] = pack_bf16x2(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
+        *reinterpret_cast<u32x2*>(optr + (32 * db + 8 * g) * 2) = w;
+      }
+  }
+}
+
+// Per-item state shared by both kernels.
+template <class T>
+struct ItemCtx {
+  ItemU it;
+  int nt;
+  int64_t head_off;
+  const char* kbase;
+  const char* vbase;
+  int qrow;
+  bool row_valid;
+};
+
+template <class T>
+__device__ __forceinline__ ItemCtx<T> begin_item(const AttnParams& p, const Lane<T>& L, uint32_t item_idx,
+                                                 int64_t row_stride_b) {
+  ItemCtx<T> c;
+  c.it = fetch_item(p.items, item_idx);
+  c.nt = (c.it.kv_len + T::BN - 1) / T::BN;
+  c.head_off = (int64_t)c.it.head * T::D * 2;
+  c.kbase = static_cast<const char*>(p.k) + (int64_t)c.it.kv_start * row_stride_b + c.head_off;
+  c.vbase = static_cast<const char*>(p.v) + (int64_t)c.it.kv_start * row_stride_b + c.head_off;
+  // Waves whose 32 rows lie past the end of a ragged query tile work on a copy of the last row and store nothing.
+  c.qrow = L.wave * 32 + L.l32;
+  c.row_valid = c.qrow < c.it.q_rows;
+  if (!c.row_valid) c.qrow = c.it.q_rows - 1;
+  return c;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel A: 4 wavefronts, 128 query rows per workgroup, two independent workgroups per compute unit.
+// Per tile every wave runs QK, softmax, PV back to back; the two workgroups of a CU overlap each
+// other's matrix and vector work without synchronising.  One barrier per tile.
+// ---------------------------------------------------------------------------------------------
 template <class T>
 __global__ void __attribute__((amdgpu_flat_work_group_size(T::NT, T::NT), amdgpu_waves_per_eu(2, 2)))
 attn_fwd_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
-  // LDS: [K0][V0][K1][V1][item index]
   lds_char* smem = (lds_char*)smem_generic;
-  volatile uint32_t* s_item = reinterpret_cast<volatile uint32_t*>(smem_generic + 4 * T::TILE_B);
+  volatile uint32_t* s_item = reinterpret_cast<volatile uint32_t*>(smem_generic + T::ITEM_OFF);
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int l32 = lane & 31;
-  const int hh = lane >> 5;
-  const int i16 = lane & 15;
-  const int b = (lane >> 4) & 1;
   const int64_t row_stride_b = (int64_t)p.n_heads * T::D * 2;
   const float c = p.c_log2;
+  Lane<T> L;
+  L.init(tid, row_stride_b);
 
-  // Loader lane constants: row inside a GROUP-row round and the global chunk this lane fetches.
-  const int lrow = wave * T::RPI + lane / T::CPR;
-  const int kcol = ((lane % T::CPR) ^ T::swz_k(lrow)) * 16;
-  const int vcol = ((lane % T::CPR) ^ T::swz_v(lrow)) * 16;
-
-  // Reader lane constants.
-  int kaddr[T::NKS];
-#pragma unroll
-  for (int ks = 0; ks < T::NKS; ++ks) kaddr[ks] = l32 * T::ROW_B + (((2 * ks + hh) ^ T::swz_k(l32)) * 16);
-  int vaddr[T::NDB];
-  {
-    const int row = 4 * hh + (i16 >> 2);
-#pragma unroll
-    for (int db = 0; db < T::NDB; ++db) {
-      const int chunk = 4 * db + 2 * b + ((i16 & 3) >> 1);
-      vaddr[db] = row * T::ROW_B + ((chunk ^ T::swz_v(row)) * 16) + 8 * (i16 & 1);
-    }
-  }
+  // The index of the next item is fetched one item ahead into the slot of the other parity; the barriers
+  // inside an item (at least two) make it visible to every wave before it is read.
+  if (tid == 0) s_item[0] = atomicAdd(p.counter, 1u) - p.counter_base;
+  wg_barrier();
+  int par = 0;
 
   for (;;) {
-    if (tid == 0) *s_item = atomicAdd(p.counter, 1u) - p.counter_base;
-    __syncthreads();
-    const uint32_t item_idx = *s_item;
+    const uint32_t item_idx = __builtin_amdgcn_readfirstlane(s_item[par]);
     if (item_idx >= p.n_items) break;
-    const WorkItem it = p.items[item_idx];
-    const int head = it.rows_head & 0xFFFF;
-    const int q_rows = (it.rows_head >> 16) & 0xFFFF;
-    const int kv_len = it.kv_len;
-    const int nt = (kv_len + T::BN - 1) / T::BN;
-    const int64_t head_off = (int64_t)head * T::D * 2;
-    const char* kbase = static_cast<const char*>(p.k) + (int64_t)it.kv_start * row_stride_b + head_off;
-    const char* vbase = static_cast<const char*>(p.v) + (int64_t)it.kv_start * row_stride_b + head_off;
+    if (tid == 0) s_item[par ^ 1] = atomicAdd(p.counter, 1u) - p.counter_base;
+    par ^= 1;
+    const ItemCtx<T> X = begin_item<T>(p, L, item_idx, row_stride_b);
+    const int kv_len = X.it.kv_len, nt = X.nt;
 
-    // Tile 0 -> buffer 0 (every wave is past the previous item's last read of it: see the barrier above).
-    if (nt == 1) tile_load<T, true>(kbase, vbase, row_stride_b, 0, kv_len, lrow, kcol, vcol, smem, smem + T::TILE_B, wave);
-    else tile_load<T, false>(kbase, vbase, row_stride_b, 0, kv_len, lrow, kcol, vcol, smem, smem + T::TILE_B, wave);
+    auto load_tile = [&](int ti) {  // K(ti), V(ti) -> buffers of parity ti&1
+      tile_load_one<T>(X.kbase, row_stride_b, ti * T::BN, kv_len, L.lrow, L.kcol, L.kvoff, smem, T::K_OFF + (ti & 1) * T::TILE_B, L.wave);
+      tile_load_one<T>(X.vbase, row_stride_b, ti * T::BN, kv_len, L.lrow, L.vcol, L.vvoff, smem, T::V_OFF + (ti & 1) * T::TILE_B, L.wave);
+    };
+    load_tile(0);
 
-    // Q fragments (B operand): lane holds query row l32 of this wave, d = 16*ks + 8*hh .. +7.
-    int qrow = wave * 32 + l32;
-    const bool row_valid = qrow < q_rows;
-    if (!row_valid) qrow = q_rows - 1;
-    const char* qptr = static_cast<const char*>(p.q) + (int64_t)(it.q_start + qrow) * row_stride_b + head_off + hh * 16;
     bf16x8 qf[T::NKS];
-#pragma unroll
-    for (int ks = 0; ks < T::NKS; ++ks) {
-      u32x4 w = *reinterpret_cast<const u32x4*>(qptr + ks * 32);
-      if (p.negate) w ^= u32x4{0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
-      qf[ks] = __builtin_bit_cast(bf16x8, w);
-    }
+    load_q<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, qf);
 
     f32x16 o[T::NDB];
 #pragma unroll
@@ -268,74 +457,180 @@ attn_fwd_kernel(AttnParams p) {
       for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
     float m_ref = -1.0e30f;  // finite, so that (m_ref - m) * 0 is 0 when scale is 0
     float l_run = 0.f;
+    f32x16 s[T::NKB];
+    uint32_t pb[T::NKB][8];
+    int ka[T::NKS], va[T::NDB];  // operand addresses in the buffers of the current tile's parity
+    L.operand_addrs((uint32_t)(uintptr_t)smem, ka, va);
 
-    const bool wave_active = wave * 32 < q_rows;
     for (int t = 0; t < nt; ++t) {
-      lds_char* kcur = smem + (t & 1) * (2 * T::TILE_B);
-      lds_char* knxt = smem + ((t & 1) ^ 1) * (2 * T::TILE_B);
       // Tile t has landed (this wave's loads), and after the barrier everyone's; everyone is also done
-      // reading the other buffer (tile t-1), so it can be refilled with tile t+1 while tile t is used.
-      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-      __syncthreads();
+      // reading the other buffers (tile t-1), so they can be refilled with tile t+1 while tile t is used.
+      wait_loads();
+      wg_barrier();
+      if (t + 1 < nt) load_tile(t + 1);
+      mfma_stream<T, false, true, kPrefetch>(smem, va, ka, pb, qf, o, s);
       if (t + 1 < nt) {
-        if (t + 2 == nt) tile_load<T, true>(kbase, vbase, row_stride_b, (t + 1) * T::BN, kv_len, lrow, kcol, vcol, knxt, knxt + T::TILE_B, wave);
-        else tile_load<T, false>(kbase, vbase, row_stride_b, (t + 1) * T::BN, kv_len, lrow, kcol, vcol, knxt, knxt + T::TILE_B, wave);
+        tile_softmax<T, false>(s, L.hh, T::BN, c, pb, o, m_ref, l_run);
+      } else {
+        tile_softmax<T, true>(s, L.hh, kv_len - t * T::BN, c, pb, o, m_ref, l_run);
       }
-      if (wave_active) {
-        const int keys_left = kv_len - t * T::BN;
-        if (keys_left >= T::BN) tile_compute<T, false>(kcur, kcur + T::TILE_B, hh, keys_left, c, kaddr, vaddr, qf, o, m_ref, l_run);
-        else tile_compute<T, true>(kcur, kcur + T::TILE_B, hh, keys_left, c, kaddr, vaddr, qf, o, m_ref, l_run);
-      }
+      mfma_stream<T, true, false, kPrefetch>(smem, va, ka, pb, qf, o, s);
+#pragma unroll
+      for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
+#pragma unroll
+      for (int db = 0; db < T::NDB; ++db) va[db] ^= T::TILE_B;
     }
 
-    // Epilogue: O^T / l -> bf16 -> out.  Lane holds d = 32*db + 8*g + 4*hh + j (i = 4*g + j) of query l32.
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (row_valid) {
-      const float inv = 1.0f / l_tot;
-      char* optr = static_cast<char*>(p.out) + (int64_t)(it.q_start + qrow) * row_stride_b + head_off + hh * 8;
-#pragma unroll
-      for (int db = 0; db < T::NDB; ++db)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          u32x2 w;
-          w[0] = pack_bf16x2(o[db][4 * g + 0] * inv, o[db][4 * g + 1] * inv);
-          w[1] = pack_bf16x2(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
-          *reinterpret_cast<u32x2*>(optr + (32 * db + 8 * g) * 2) = w;
-        }
-    }
-    // The next item's first loads overwrite buffer 0 and the item slot: wait until every wave has left the tile loop.
-    __syncthreads();
+    store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run);
+    wg_barrier();  // the next item's first loads overwrite the buffers of parity 0
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Kernel B (ping-pong): 8 wavefronts, 256 query rows per workgroup, one workgroup per compute unit.
+//
+// Wavefronts w and w+4 share a SIMD.  Group 0 (waves 0-3) and group 1 (waves 4-7) run the same
+// per-tile program  softmax(t) | PV(t) + QK(t+1)  but one phase apart, with a workgroup barrier
+// after every phase: while one group keeps the matrix pipe busy (32 MFMAs), the other does its
+// softmax on the vector ALU.  Phase p of an item (p = 0 after the first barrier):
+//     group 0:  QK(0) at p=0,  softmax(t) at p=2t+1,  PV(t)+QK(t+1) at p=2t+2
+//     group 1:  idle  at p=0,  QK(0) at p=1, softmax(t) at p=2t+2, PV(t)+QK(t+1) at p=2t+3
+// K(t+1) and V(t) are therefore read in phases 2t+2 and 2t+3 only; their buffers (parity of the
+// tile index) are refilled with K(t+3) / V(t+2) from phase 2t+4 on.  The pair {K(t+2), V(t+1)} is
+// issued at the start of phase 2t+2 and must have landed by the end of phase 2t+3; each group
+// issues at the start of, and waits at the end of, whatever it runs in those phases.
+// ---------------------------------------------------------------------------------------------
 template <class T>
+__global__ void __attribute__((amdgpu_flat_work_group_size(T::NT, T::NT), amdgpu_waves_per_eu(2, 2)))
+attn_fwd_pp_kernel(AttnParams p) {
+  static_assert(T::NWAVES == 8, "two groups of four wavefronts");
+  extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+  lds_char* smem = (lds_char*)smem_generic;
+  volatile uint32_t* s_item = reinterpret_cast<volatile uint32_t*>(smem_generic + T::ITEM_OFF);
+
+  const int tid = threadIdx.x;
+  const int64_t row_stride_b = (int64_t)p.n_heads * T::D * 2;
+  const float c = p.c_log2;
+  Lane<T> L;
+  L.init(tid, row_stride_b);
+  const int group = L.wave >> 2;
+
+  // The index of the next item is fetched one item ahead into the slot of the other parity; the barriers
+  // inside an item (at least three) make it visible to every wave before it is read.
+  if (tid == 0) s_item[0] = atomicAdd(p.counter, 1u) - p.counter_base;
+  wg_barrier();
+  int par = 0;
+
+  for (;;) {
+    const uint32_t item_idx = __builtin_amdgcn_readfirstlane(s_item[par]);
+    if (item_idx >= p.n_items) break;
+    if (tid == 0) s_item[par ^ 1] = atomicAdd(p.counter, 1u) - p.counter_base;
+    par ^= 1;
+    const ItemCtx<T> X = begin_item<T>(p, L, item_idx, row_stride_b);
+    const int kv_len = X.it.kv_len, nt = X.nt;
+
+    auto load_k = [&](int ti) {  // K(ti) -> K buffer of parity ti&1
+      tile_load_one<T>(X.kbase, row_stride_b, ti * T::BN, kv_len, L.lrow, L.kcol, L.kvoff, smem, T::K_OFF + (ti & 1) * T::TILE_B, L.wave);
+    };
+    auto load_v = [&](int ti) {  // V(ti) -> V buffer of parity ti&1
+      tile_load_one<T>(X.vbase, row_stride_b, ti * T::BN, kv_len, L.lrow, L.vcol, L.vvoff, smem, T::V_OFF + (ti & 1) * T::TILE_B, L.wave);
+    };
+    auto load_pair = [&](int t) {  // what phases 2t+2 / 2t+3 read: K(t+1) and V(t)
+      if (t + 1 < nt) load_k(t + 1);
+      load_v(t);
+    };
+
+    load_k(0);
+    load_pair(0);
+
+    bf16x8 qf[T::NKS];
+    load_q<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, qf);
+
+    f32x16 o[T::NDB];
+#pragma unroll
+    for (int db = 0; db < T::NDB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+    float m_ref = -1.0e30f;  // finite, so that (m_ref - m) * 0 is 0 when scale is 0
+    float l_run = 0.f;
+    f32x16 s[T::NKB];
+    uint32_t pb[T::NKB][8];
+    int ka[T::NKS], va[T::NDB];  // ka: K buffer the next QK reads; va: V buffer the next PV reads
+    L.operand_addrs((uint32_t)(uintptr_t)smem, ka, va);
+
+    wait_loads();
+    wg_barrier();                  // K(0), K(1), V(0) of every wave have landed; phase 0 starts
+    if (group == 1) wg_barrier();  // group 1 idles in phase 0
+    mfma_stream<T, false, true, kPrefetch>(smem, va, ka, pb, qf, o, s);  // QK(0)
+#pragma unroll
+    for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
+    wg_barrier();
+
+    for (int t = 0; t + 1 < nt; ++t) {
+      // ---- vector phase: softmax(t), a full tile
+      if (group == 1) load_pair(t + 1);
+      tile_softmax<T, false>(s, L.hh, T::BN, c, pb, o, m_ref, l_run);
+      if (group == 0) wait_loads();  // pair t (issued one matrix phase ago, or before the item's first barrier)
+      wg_barrier();
+      // ---- matrix phase: PV(t), QK(t+1)
+      if (group == 0) load_pair(t + 1);
+      __builtin_amdgcn_s_setprio(1);
+      mfma_stream<T, true, true, kPrefetch>(smem, va, ka, pb, qf, o, s);
+      __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+      for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
+#pragma unroll
+      for (int db = 0; db < T::NDB; ++db) va[db] ^= T::TILE_B;
+      if (group == 1) wait_loads();  // pair t+1 (issued at the start of this group's softmax(t))
+      wg_barrier();
+    }
+    // ---- last tile: masked softmax, PV only
+    tile_softmax<T, true>(s, L.hh, kv_len - (nt - 1) * T::BN, c, pb, o, m_ref, l_run);
+    wg_barrier();
+    __builtin_amdgcn_s_setprio(1);
+    mfma_stream<T, true, false, kPrefetch>(smem, va, ka, pb, qf, o, s);
+    __builtin_amdgcn_s_setprio(0);
+    wg_barrier();
+
+    store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run);
+    if (group == 0) wg_barrier();  // group 0 idles (after its stores) while group 1 runs its last matrix phase
+  }
+}
+
+template <class T, void (*KERNEL)(AttnParams)>
 static hipError_t launch_t(const AttnParams& p, int grid, hipStream_t stream) {
   static bool attr_set[16] = {};
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= 16 || !attr_set[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            T::LDS_BYTES);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(KERNEL), hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 16) attr_set[dev] = true;
   }
-  hipLaunchKernelGGL(attn_fwd_kernel<T>, dim3(grid), dim3(T::NT), T::LDS_BYTES, stream, p);
+  hipLaunchKernelGGL(KERNEL, dim3(grid), dim3(T::NT), T::LDS_BYTES, stream, p);
   return hipGetLastError();
 }
 
-int attn_fwd_block_m(int head_dim) {
-  (void)head_dim;
-  return 128;
-}
-int attn_fwd_wgs_per_cu(int head_dim) {
-  (void)head_dim;
-  return 2;
+int attn_fwd_block_m(AttnKernel kernel) { return kernel == AttnKernel::kPingPong256 ? 256 : 128; }
+int attn_fwd_wgs_per_cu(AttnKernel kernel) { return kernel == AttnKernel::kPingPong256 ? 1 : 2; }
+
+AttnKernel attn_fwd_select(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int n_cus) {
+  // The ping-pong kernel needs at least one 256-row item per compute unit; smaller packs run the 128-row kernel,
+  // which cuts them into twice as many items.
+  int64_t items256 = 0;
+  for (int32_t i = 0; i < n_seqs; ++i) items256 += (int64_t)((cu_seqlens[i + 1] - cu_seqlens[i] + 255) / 256) * n_heads;
+  return items256 >= n_cus ? AttnKernel::kPingPong256 : AttnKernel::kIndependent128;
 }
 
-hipError_t attn_fwd_launch(const AttnParams& p, int head_dim, int grid, hipStream_t stream) {
-  if (head_dim == 128) return launch_t<Tile<128, 4, 64>>(p, grid, stream);
-  if (head_dim == 64) return launch_t<Tile<64, 4, 64>>(p, grid, stream);
+hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim, int grid, hipStream_t stream) {
+  if (kernel == AttnKernel::kPingPong256) {
+    if (head_dim == 128) return launch_t<Tile<128, 8, 64>, attn_fwd_pp_kernel<Tile<128, 8, 64>>>(p, grid, stream);
+    if (head_dim == 64) return launch_t<Tile<64, 8, 64>, attn_fwd_pp_kernel<Tile<64, 8, 64>>>(p, grid, stream);
+  } else {
+    if (head_dim == 128) return launch_t<Tile<128, 4, 64>, attn_fwd_kernel<Tile<128, 4, 64>>>(p, grid, stream);
+    if (head_dim == 64) return launch_t<Tile<64, 4, 64>, attn_fwd_kernel<Tile<64, 4, 64>>>(p, grid, stream);
+  }
   return hipErrorInvalidValue;
 }
 

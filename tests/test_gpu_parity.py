@@ -132,6 +132,22 @@ def test_pack_isolation_bitwise(runner):
     assert not np.array_equal(pert[200:533], full[200:533])
 
 
+def test_both_kernels_give_the_same_bits(runner):
+    """A large pack runs the 256-row ping-pong kernel, a small one the 128-row kernel: same bits per sequence."""
+    w = make_custom([8192, 300, 77], 8, 64, seed=28)
+    items, bm = da.dit_attn_plan(w.cu_seqlens, 8, 64)
+    assert bm == 256
+    full = runner.run(w)
+    for s, e in ((8192, 8492), (8492, 8569)):
+        alone = make_custom([e - s], 8, 64, seed=0)
+        alone.q, alone.k, alone.v = w.q[s:e].copy(), w.k[s:e].copy(), w.v[s:e].copy()
+        assert da.dit_attn_plan(alone.cu_seqlens, 8, 64)[1] == 128
+        assert np.array_equal(runner.run(alone), full[s:e])
+    rows = sample_rows(w.cu_seqlens, seed=3, block=256)
+    ref = orc.attention_varlen_rows(w.q, w.k, w.v, w.cu_seqlens, w.scale, rows)
+    assert_parity(full[rows], ref, "ping-pong kernel, head_dim 64")
+
+
 def test_head_subset_equals_heads_of_wider_run(runner):
     """The head-split shard view: running heads [10, 20) alone equals those heads of a 40-head run."""
     w = make_custom([700], 40, 128, seed=22)
