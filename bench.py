@@ -26,6 +26,11 @@ from dit_workloads import CONFIG_NAMES, attention_flops, make_workload, sample_r
 MFMA_BF16_PEAK_TFLOPS = 2516.6
 DEFAULT_WORKLOAD = "mixed_varlen"
 
+# HBM bytes per launch (fetch + write) from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this file,
+# each scaled by what the same counter reads for the 1 GiB copy of --copy-calibration; the summaries and the
+# commands are under profiles/.  None where no such run has been made for the workload.
+MEASURED_HBM_BYTES = {}
+
 
 def _to_dev(bits, torch):
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to("cuda").view(torch.bfloat16)
@@ -58,7 +63,7 @@ def time_workload(da, torch, ctx, w, steps: int, warmup: int):
     return (t1 - t0) * 1e3 / steps, float(np.mean(per)), per, out
 
 
-def cpu_baseline(w, budget_s: float = 20.0):
+def cpu_baseline(w, budget_s: float = 40.0):
     """The fp64 oracle, as it stands, on a bounded row sample of the same workload."""
     from oracle import dit_attn_oracle as orc
     try:
@@ -67,13 +72,14 @@ def cpu_baseline(w, budget_s: float = 20.0):
     except Exception:
         threads = len(os.sched_getaffinity(0))
     lens = np.diff(w.cu_seqlens)
-    # calibrate on a few rows, then size the sample to the budget
-    rows = sample_rows(w.cu_seqlens, seed=w.seed, block=64, max_rows=24)
+    # calibrate on a few hundred rows, then size the sample (one row per `block` rows) to the budget
+    rows = sample_rows(w.cu_seqlens, seed=w.seed, block=256)
     t0 = time.perf_counter()
     orc.attention_varlen_rows(w.q, w.k, w.v, w.cu_seqlens, w.scale, rows)
     t_cal = time.perf_counter() - t0
-    n_rows = int(min(max(24, len(rows) * budget_s / max(t_cal, 1e-3)), 4096, w.total_tokens))
-    rows = sample_rows(w.cu_seqlens, seed=w.seed + 1, block=64, max_rows=n_rows)
+    n_rows = int(min(max(len(rows), len(rows) * budget_s / max(t_cal, 1e-3)), w.total_tokens))
+    block = max(1, w.total_tokens // n_rows)
+    rows = sample_rows(w.cu_seqlens, seed=w.seed + 1, block=block)
     t0 = time.perf_counter()
     orc.attention_varlen_rows(w.q, w.k, w.v, w.cu_seqlens, w.scale, rows)
     dt = time.perf_counter() - t0
@@ -98,6 +104,8 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other configurations (reported under per_config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a 1 GiB device-to-device copy (a kernel of known HBM traffic, for counter scaling)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -111,6 +119,15 @@ def main():
         sys.exit(3)
     da.load_library()
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4, "copy_calibration_bytes_written": src.numel() * 4,
+                          "launches": 3}), flush=True)
+        return
     ctx = da.dit_attn_create(0)
 
     w = make_workload(args.workload, args.seed)
@@ -118,6 +135,9 @@ def main():
     wall_ms, kern_ms, per, _ = time_workload(da, torch, ctx, w, args.steps, args.warmup)
     tflops = flops / (wall_ms * 1e-3) / 1e12
     kern_tflops = flops / (kern_ms * 1e-3) / 1e12
+
+    _, block_m = da.dit_attn_plan(w.cu_seqlens, w.n_heads, w.head_dim)
+    kernel_name = ("attn_fwd_pp_kernel<Tile<%d,8,64>>" if block_m == 256 else "attn_fwd_kernel<Tile<%d,4,64>>") % w.head_dim
 
     result = {
         "metric": "DiT attention TFLOP/s per denoising step (bf16) and % of MFMA peak, 1 GPU",
@@ -146,12 +166,12 @@ def main():
         "step_ms_cv_pct": round(100.0 * float(np.std(per) / np.mean(per)), 3),
         "roofline": {
             "bound": "mfma",
-            "kernel": "attn_fwd_kernel",
+            "kernel": kernel_name,
             "achieved": round(kern_tflops, 2),
             "peak": MFMA_BF16_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(kern_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-            "traffic": None,
+            "traffic": MEASURED_HBM_BYTES.get(w.name),
             "kernel_ms_avg": round(kern_ms, 4),
             "algorithmic_hbm_bytes": int(4 * w.total_tokens * w.n_heads * w.head_dim * 2),
         },

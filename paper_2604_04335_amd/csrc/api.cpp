@@ -37,8 +37,7 @@ thread_local std::string g_create_error;
 struct dit_attn_ctx {
   int device = 0;
   int n_cus = 0;
-  uint32_t* counter = nullptr;  // device; value is tracked on the host in counter_value
-  uint32_t counter_value = 0;
+  uint32_t* sync = nullptr;     // device, 2 words: items taken, workgroups finished; zero between launches
   uint64_t tick = 0;
   std::vector<std::unique_ptr<CachedPlan>> plans;
   std::string error;
@@ -134,12 +133,12 @@ int dit_attn_create(dit_attn_ctx** out_ctx, int device_id) {
   ctx->n_cus = prop.multiProcessorCount;
   DeviceGuard guard;
   e = guard.enter(device_id);
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->counter), sizeof(uint32_t));
-  if (e == hipSuccess) e = hipMemset(ctx->counter, 0, sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->sync), 2 * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMemset(ctx->sync, 0, 2 * sizeof(uint32_t));
   if (e != hipSuccess) {
     (void)hipGetLastError();
     g_create_error = std::string("context set-up: ") + hipGetErrorString(e);
-    if (ctx->counter) (void)hipFree(ctx->counter);
+    if (ctx->sync) (void)hipFree(ctx->sync);
     delete ctx;
     return DIT_ATTN_ERR_HIP;
   }
@@ -153,7 +152,7 @@ void dit_attn_destroy(dit_attn_ctx* ctx) {
   if (guard.enter(ctx->device) == hipSuccess) {
     for (auto& p : ctx->plans)
       if (p->dev_items) (void)hipFree(p->dev_items);
-    if (ctx->counter) (void)hipFree(ctx->counter);
+    if (ctx->sync) (void)hipFree(ctx->sync);
   }
   (void)hipGetLastError();
   delete ctx;
@@ -261,16 +260,13 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
   p.v = v;
   p.out = out;
   p.items = plan->dev_items;
-  p.counter = ctx->counter;
-  p.counter_base = ctx->counter_value;
+  p.sync = ctx->sync;
   p.n_items = n_items;
   p.n_heads = n_heads;
   p.c_log2 = std::fabs(scale) * 1.44269504088896340736f;
   p.negate = scale < 0.f ? 1 : 0;
   e = dit::attn_fwd_launch(p, plan->kernel, head_dim, grid, s);
   if (e != hipSuccess) return fail_hip(ctx, e, "kernel launch");
-  // Every workgroup takes one value past the end of the list before it exits.
-  ctx->counter_value += n_items + static_cast<uint32_t>(grid);
   return DIT_ATTN_OK;
 }
 

@@ -13,8 +13,9 @@ struct AttnParams {
   const void* v;
   void* out;                // bf16 [T, H, D]
   const WorkItem* items;    // device work-list
-  uint32_t* counter;        // device work counter (monotonic; see counter_base)
-  uint32_t counter_base;    // value of *counter when this launch starts
+  uint32_t* sync;           // device, 2 words: [0] items taken so far, [1] workgroups finished.  Both are zero
+                            // between launches: the last workgroup to finish clears them (so a launch can be
+                            // replayed from a captured graph, and the host keeps no count).
   uint32_t n_items;
   int32_t n_heads;
   float c_log2;             // |scale| * log2(e)
@@ -34,8 +35,7 @@ AttnKernel attn_fwd_select(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_
 int attn_fwd_block_m(AttnKernel kernel);
 int attn_fwd_wgs_per_cu(AttnKernel kernel);
 
-// Enqueue the forward kernel with `grid` persistent workgroups.  Every workgroup takes exactly one
-// counter value at or beyond n_items, so the counter ends at counter_base + n_items + grid.
+// Enqueue the forward kernel with `grid` persistent workgroups.
 hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim, int grid, hipStream_t stream);
 
 }  // namespace dit

@@ -331,6 +331,18 @@ __device__ __forceinline__ void tile_softmax(f32x16 (&s)[T::NKB], int hh, int ke
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Work distribution: thread 0 of a workgroup takes the next list index; indices at or past n_items end the workgroup.
+__device__ __forceinline__ uint32_t take_item(const AttnParams& p) { return atomicAdd(&p.sync[0], 1u); }
+// After the item loop: the last workgroup to get here clears both words for the next launch.
+__device__ __forceinline__ void finish_workgroup(const AttnParams& p) {
+  __threadfence();
+  const uint32_t done = atomicAdd(&p.sync[1], 1u);
+  if (done == gridDim.x - 1) {
+    p.sync[0] = 0u;
+    p.sync[1] = 0u;
+  }
+}
+
 // Work item fields, wave-uniform.
 struct ItemU {
   int q_start, kv_start, kv_len, head, q_rows;
@@ -429,14 +441,14 @@ attn_fwd_kernel(AttnParams p) {
 
   // The index of the next item is fetched one item ahead into the slot of the other parity; the barriers
   // inside an item (at least two) make it visible to every wave before it is read.
-  if (tid == 0) s_item[0] = atomicAdd(p.counter, 1u) - p.counter_base;
+  if (tid == 0) s_item[0] = take_item(p);
   wg_barrier();
   int par = 0;
 
   for (;;) {
     const uint32_t item_idx = __builtin_amdgcn_readfirstlane(s_item[par]);
     if (item_idx >= p.n_items) break;
-    if (tid == 0) s_item[par ^ 1] = atomicAdd(p.counter, 1u) - p.counter_base;
+    if (tid == 0) s_item[par ^ 1] = take_item(p);
     par ^= 1;
     const ItemCtx<T> X = begin_item<T>(p, L, item_idx, row_stride_b);
     const int kv_len = X.it.kv_len, nt = X.nt;
@@ -484,6 +496,7 @@ attn_fwd_kernel(AttnParams p) {
     store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run);
     wg_barrier();  // the next item's first loads overwrite the buffers of parity 0
   }
+  if (tid == 0) finish_workgroup(p);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -517,14 +530,14 @@ attn_fwd_pp_kernel(AttnParams p) {
 
   // The index of the next item is fetched one item ahead into the slot of the other parity; the barriers
   // inside an item (at least three) make it visible to every wave before it is read.
-  if (tid == 0) s_item[0] = atomicAdd(p.counter, 1u) - p.counter_base;
+  if (tid == 0) s_item[0] = take_item(p);
   wg_barrier();
   int par = 0;
 
   for (;;) {
     const uint32_t item_idx = __builtin_amdgcn_readfirstlane(s_item[par]);
     if (item_idx >= p.n_items) break;
-    if (tid == 0) s_item[par ^ 1] = atomicAdd(p.counter, 1u) - p.counter_base;
+    if (tid == 0) s_item[par ^ 1] = take_item(p);
     par ^= 1;
     const ItemCtx<T> X = begin_item<T>(p, L, item_idx, row_stride_b);
     const int kv_len = X.it.kv_len, nt = X.nt;
@@ -595,6 +608,7 @@ attn_fwd_pp_kernel(AttnParams p) {
     store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run);
     if (group == 0) wg_barrier();  // group 0 idles (after its stores) while group 1 runs its last matrix phase
   }
+  if (tid == 0) finish_workgroup(p);
 }
 
 template <class T, void (*KERNEL)(AttnParams)>
