@@ -29,7 +29,11 @@ DEFAULT_WORKLOAD = "mixed_varlen"
 # HBM bytes per launch (fetch + write) from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this file,
 # each scaled by what the same counter reads for the 1 GiB copy of --copy-calibration; the summaries and the
 # commands are under profiles/.  None where no such run has been made for the workload.
-MEASURED_HBM_BYTES = {}
+MEASURED_HBM_BYTES = {
+    "mixed_varlen": 2_456_016_281,  # fetch 1047846.3 KiB x 2.000 + write 302760.8 KiB x 1.000
+    "sp_shard": 4_510_498_509,      # fetch 2103992.4 KiB x 2.000 + write 196798.9 KiB x 1.000
+    "t2v_single": 1_365_433_140,    # fetch 604196.2 KiB x 2.000 + write 125038.4 KiB x 1.000
+}
 
 
 def _to_dev(bits, torch):
