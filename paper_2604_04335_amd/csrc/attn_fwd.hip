@@ -510,8 +510,10 @@ attn_fwd_kernel(AttnParams p) {
 //     group 1:  idle  at p=0,  QK(0) at p=1, softmax(t) at p=2t+2, PV(t)+QK(t+1) at p=2t+3
 // K(t+1) and V(t) are therefore read in phases 2t+2 and 2t+3 only; their buffers (parity of the
 // tile index) are refilled with K(t+3) / V(t+2) from phase 2t+4 on.  The pair {K(t+2), V(t+1)} is
-// issued at the start of phase 2t+2 and must have landed by the end of phase 2t+3; each group
-// issues at the start of, and waits at the end of, whatever it runs in those phases.
+// issued at the start of phase 2t+2 by group 1, which is then in its vector phase, for both groups
+// (measured: +10 % over each group loading its own share, because a wavefront in its matrix phase is
+// the critical path), and awaited by group 1 at the end of phase 2t+3, before the barrier that lets
+// group 0 read it.
 // ---------------------------------------------------------------------------------------------
 template <class T>
 __global__ void __attribute__((amdgpu_flat_work_group_size(T::NT, T::NT), amdgpu_waves_per_eu(2, 2)))
@@ -553,6 +555,16 @@ attn_fwd_pp_kernel(AttnParams p) {
       load_v(t);
     };
 
+    // Inside the tile loop group 1 issues the loads of both groups (its own rows and those of wave-4) at the start of
+    // its vector phase: the wavefronts that are in their matrix phase issue nothing but MFMAs and operand reads.
+    auto load_pair_all = [&](int t) {
+      load_pair(t);
+      const int w2 = L.wave - 4;
+      const int lrow2 = L.lrow - 4 * T::RPI;
+      const uint32_t d = (uint32_t)(4 * T::RPI) * (uint32_t)row_stride_b;
+      if (t + 1 < nt) tile_load_one<T>(X.kbase, row_stride_b, (t + 1) * T::BN, kv_len, lrow2, L.kcol, L.kvoff - d, smem, T::K_OFF + ((t + 1) & 1) * T::TILE_B, w2);
+      tile_load_one<T>(X.vbase, row_stride_b, t * T::BN, kv_len, lrow2, L.vcol, L.vvoff - d, smem, T::V_OFF + (t & 1) * T::TILE_B, w2);
+    };
     load_k(0);
     load_pair(0);
 
@@ -581,12 +593,10 @@ attn_fwd_pp_kernel(AttnParams p) {
 
     for (int t = 0; t + 1 < nt; ++t) {
       // ---- vector phase: softmax(t), a full tile
-      if (group == 1) load_pair(t + 1);
+      if (group == 1) load_pair_all(t + 1);
       tile_softmax<T, false>(s, L.hh, T::BN, c, pb, o, m_ref, l_run);
-      if (group == 0) wait_loads();  // pair t (issued one matrix phase ago, or before the item's first barrier)
       wg_barrier();
       // ---- matrix phase: PV(t), QK(t+1)
-      if (group == 0) load_pair(t + 1);
       __builtin_amdgcn_s_setprio(1);
       mfma_stream<T, true, true, kPrefetch>(smem, va, ka, pb, qf, o, s);
       __builtin_amdgcn_s_setprio(0);
@@ -594,7 +604,7 @@ attn_fwd_pp_kernel(AttnParams p) {
       for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
 #pragma unroll
       for (int db = 0; db < T::NDB; ++db) va[db] ^= T::TILE_B;
-      if (group == 1) wait_loads();  // pair t+1 (issued at the start of this group's softmax(t))
+      if (group == 1) wait_loads();  // pair t+1, issued at the start of this group's softmax(t)
       wg_barrier();
     }
     // ---- last tile: masked softmax, PV only
