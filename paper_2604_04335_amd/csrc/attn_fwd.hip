@@ -181,16 +181,17 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// The MFMA stream of one tile step: optionally O^T += V^T P^T (V tile addressed by va), then optionally
-// S^T = K Q^T (K tile addressed by ka).  Operand reads run PD MFMAs ahead of their use, through a ring of PD
-// operand registers.
-template <class T, bool DO_PV, bool DO_QK, int PD>
+// An MFMA stream: optionally O^T += V^T P^T (V tile addressed by va), then steps [Q0, Q1) of S^T = K Q^T (K tile
+// addressed by ka; step q is k-step q / NKB of key block q % NKB, and step 0 of a block starts it from zero).
+// Operand reads run PD MFMAs ahead of their use, through a ring of PD operand registers.
+template <class T, bool DO_PV, int Q0, int Q1, int PD>
 __device__ __forceinline__ void mfma_stream(lds_char* smem, const int (&va)[T::NDB], const int (&ka)[T::NKS],
                                             const uint32_t (&pb)[T::NKB][8], const bf16x8 (&qf)[T::NKS],
                                             f32x16 (&o)[T::NDB], f32x16 (&s)[T::NKB]) {
   constexpr int NPV = DO_PV ? T::NPV : 0;
-  constexpr int NQK = DO_QK ? T::NQK : 0;
+  constexpr int NQK = Q1 - Q0;
   constexpr int N = NPV + NQK;
+  static_assert(Q0 >= 0 && Q0 <= Q1 && Q1 <= T::NQK, "QK step range");
   bf16x8 frag[PD];
   int va_[T::NDB], ka_[T::NKS];
 #pragma unroll
@@ -207,7 +208,7 @@ __device__ __forceinline__ void mfma_stream(lds_char* smem, const int (&va)[T::N
       const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * T::ROW_B));
       frag[J % PD] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     } else {  // QK step: ks = q / NKB, kb = q % NKB (kb fastest: consecutive MFMAs use different accumulators)
-      constexpr int q = J - NPV, ks = q / T::NKB, kb = q % T::NKB;
+      constexpr int q = Q0 + J - NPV, ks = q / T::NKB, kb = q % T::NKB;
       frag[J % PD] = *(lds_bf16x8*)(uintptr_t)(uint32_t)(ka_[ks] + kb * 32 * T::ROW_B);
     }
   };
@@ -218,7 +219,7 @@ __device__ __forceinline__ void mfma_stream(lds_char* smem, const int (&va)[T::N
       u32x4 pw = {pb[kb][4 * u], pb[kb][4 * u + 1], pb[kb][4 * u + 2], pb[kb][4 * u + 3]};
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], __builtin_bit_cast(bf16x8, pw), o[db], 0, 0, 0);
     } else {
-      constexpr int q = J - NPV, ks = q / T::NKB, kb = q % T::NKB;
+      constexpr int q = Q0 + J - NPV, ks = q / T::NKB, kb = q % T::NKB;
       if constexpr (ks == 0) {
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], qf[ks], zero, 0, 0, 0);
@@ -243,11 +244,11 @@ __device__ __forceinline__ void mfma_stream(lds_char* smem, const int (&va)[T::N
         if constexpr (R < NPV) {
           asm volatile("" : "+v"(va_[R % T::NDB]) : "v"(o[dbj]));
         } else {
-          asm volatile("" : "+v"(ka_[(R - NPV) / T::NKB]) : "v"(o[dbj]));
+          asm volatile("" : "+v"(ka_[(Q0 + R - NPV) / T::NKB]) : "v"(o[dbj]));
         }
       } else {
-        constexpr int kbj = (J - NPV) % T::NKB;
-        asm volatile("" : "+v"(ka_[(R - NPV) / T::NKB]) : "v"(s[kbj]));
+        constexpr int kbj = (Q0 + J - NPV) % T::NKB;
+        asm volatile("" : "+v"(ka_[(Q0 + R - NPV) / T::NKB]) : "v"(s[kbj]));
       }
     }
   };
@@ -480,13 +481,13 @@ attn_fwd_kernel(AttnParams p) {
       wait_loads();
       wg_barrier();
       if (t + 1 < nt) load_tile(t + 1);
-      mfma_stream<T, false, true, kPrefetch>(smem, va, ka, pb, qf, o, s);
+      mfma_stream<T, false, 0, T::NQK, kPrefetch>(smem, va, ka, pb, qf, o, s);
       if (t + 1 < nt) {
         tile_softmax<T, false>(s, L.hh, T::BN, c, pb, o, m_ref, l_run);
       } else {
         tile_softmax<T, true>(s, L.hh, kv_len - t * T::BN, c, pb, o, m_ref, l_run);
       }
-      mfma_stream<T, true, false, kPrefetch>(smem, va, ka, pb, qf, o, s);
+      mfma_stream<T, true, 0, 0, kPrefetch>(smem, va, ka, pb, qf, o, s);
 #pragma unroll
       for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
 #pragma unroll
@@ -586,7 +587,7 @@ attn_fwd_pp_kernel(AttnParams p) {
     wait_loads();
     wg_barrier();                  // K(0), K(1), V(0) of every wave have landed; phase 0 starts
     if (group == 1) wg_barrier();  // group 1 idles in phase 0
-    mfma_stream<T, false, true, kPrefetch>(smem, va, ka, pb, qf, o, s);  // QK(0)
+    mfma_stream<T, false, 0, T::NQK, kPrefetch>(smem, va, ka, pb, qf, o, s);  // QK(0)
 #pragma unroll
     for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
     wg_barrier();
@@ -598,7 +599,7 @@ attn_fwd_pp_kernel(AttnParams p) {
       wg_barrier();
       // ---- matrix phase: PV(t), QK(t+1)
       __builtin_amdgcn_s_setprio(1);
-      mfma_stream<T, true, true, kPrefetch>(smem, va, ka, pb, qf, o, s);
+      mfma_stream<T, true, 0, T::NQK, kPrefetch>(smem, va, ka, pb, qf, o, s);
       __builtin_amdgcn_s_setprio(0);
 #pragma unroll
       for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
@@ -611,7 +612,7 @@ attn_fwd_pp_kernel(AttnParams p) {
     tile_softmax<T, true>(s, L.hh, kv_len - (nt - 1) * T::BN, c, pb, o, m_ref, l_run);
     wg_barrier();
     __builtin_amdgcn_s_setprio(1);
-    mfma_stream<T, true, false, kPrefetch>(smem, va, ka, pb, qf, o, s);
+    mfma_stream<T, true, 0, 0, kPrefetch>(smem, va, ka, pb, qf, o, s);
     __builtin_amdgcn_s_setprio(0);
     wg_barrier();
 
