@@ -43,6 +43,7 @@ extern "C" {
 #define DIT_ATTN_ERR_N_HEADS       (-6)  /* n_heads < 1 or > 65535 */
 #define DIT_ATTN_ERR_ALIGN         (-7)  /* q, k, v or out is not 16-byte aligned */
 #define DIT_ATTN_ERR_CAPACITY      (-8)  /* output buffer of dit_attn_plan too small */
+#define DIT_ATTN_ERR_KERNEL        (-9)  /* dit_attn_set_kernel: no such kernel */
 
 typedef struct dit_attn_ctx dit_attn_ctx; /* opaque */
 
@@ -95,6 +96,27 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx,
  * have synchronised every stream the context was used on.  NULL is a no-op.
  */
 void dit_attn_destroy(dit_attn_ctx* ctx);
+
+/*
+ * Kernel choice of a context.  The library has three kernels for the same
+ * operation (which one is fastest depends on the pack, Section 4.3 / Table 3:
+ * image steps are short, video steps long):
+ *     DIT_ATTN_KERNEL_AUTO   (-1) chosen per pack: packs with at least one
+ *                                 256-row tile per compute unit run a 256-row
+ *                                 kernel, smaller ones the 128-row kernel
+ *     DIT_ATTN_KERNEL_128     (0) 128 query rows per tile
+ *     DIT_ATTN_KERNEL_PINGPONG(1) 256 rows per tile, two alternating groups
+ *     DIT_ATTN_KERNEL_WIDE    (2) 256 rows per tile, 64 per wavefront
+ * The three kernels do the same arithmetic in the same order: their results
+ * agree bit for bit.  A forced kernel applies to later calls on
+ * `ctx`; meant for tests and measurements.
+ * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL or DIT_ATTN_ERR_KERNEL.
+ */
+#define DIT_ATTN_KERNEL_AUTO     (-1)
+#define DIT_ATTN_KERNEL_128        0
+#define DIT_ATTN_KERNEL_PINGPONG   1
+#define DIT_ATTN_KERNEL_WIDE       2
+int dit_attn_set_kernel(dit_attn_ctx* ctx, int kernel);
 
 /*
  * Text of the last error recorded in `ctx` (or of the last failed

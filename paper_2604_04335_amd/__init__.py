@@ -26,6 +26,11 @@ __all__ = [
     "dit_attn_destroy",
     "dit_attn_last_error",
     "dit_attn_plan",
+    "dit_attn_set_kernel",
+    "KERNEL_AUTO",
+    "KERNEL_128",
+    "KERNEL_PINGPONG",
+    "KERNEL_WIDE",
     "DitAttention",
 ]
 
@@ -42,6 +47,7 @@ ERROR_NAMES = {
     -6: "DIT_ATTN_ERR_N_HEADS",
     -7: "DIT_ATTN_ERR_ALIGN",
     -8: "DIT_ATTN_ERR_CAPACITY",
+    -9: "DIT_ATTN_ERR_KERNEL",
 }
 
 
@@ -76,6 +82,8 @@ def load_library() -> ctypes.CDLL:
     lib.dit_attn_destroy.argtypes = [vp]
     lib.dit_attn_last_error.restype = ctypes.c_char_p
     lib.dit_attn_last_error.argtypes = [vp]
+    lib.dit_attn_set_kernel.restype = ctypes.c_int
+    lib.dit_attn_set_kernel.argtypes = [vp, ctypes.c_int]
     lib.dit_attn_plan.restype = i64
     lib.dit_attn_plan.argtypes = [i32p, i32, i32, i32, i32p, i64, i32p]
     _LIB = lib
@@ -114,6 +122,16 @@ def dit_attn_create(device_id: int = 0) -> int:
     if rc != 0:
         raise DitAttnError(rc, dit_attn_last_error(None))
     return int(h.value)
+
+
+KERNEL_AUTO, KERNEL_128, KERNEL_PINGPONG, KERNEL_WIDE = -1, 0, 1, 2
+
+
+def dit_attn_set_kernel(ctx, kernel: int) -> None:
+    """Force one of the library's kernels for later calls on `ctx` (KERNEL_AUTO: chosen per pack)."""
+    rc = load_library().dit_attn_set_kernel(ctypes.c_void_p(ctx), int(kernel))
+    if rc != 0:
+        raise DitAttnError(rc, dit_attn_last_error(ctx))
 
 
 def dit_attn_destroy(ctx) -> None:

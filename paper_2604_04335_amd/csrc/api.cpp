@@ -39,6 +39,7 @@ struct dit_attn_ctx {
   int n_cus = 0;
   uint32_t* sync = nullptr;     // device, 2 words: items taken, workgroups finished; zero between launches
   uint64_t tick = 0;
+  int force_kernel = -1;        // -1: chosen per pack; else a dit::AttnKernel value (dit_attn_set_kernel)
   std::vector<std::unique_ptr<CachedPlan>> plans;
   std::string error;
 };
@@ -158,6 +159,14 @@ void dit_attn_destroy(dit_attn_ctx* ctx) {
   delete ctx;
 }
 
+int dit_attn_set_kernel(dit_attn_ctx* ctx, int kernel) {
+  if (!ctx) return DIT_ATTN_ERR_NULL;
+  if (kernel < -1 || kernel > static_cast<int>(dit::AttnKernel::kWide256))
+    return fail(ctx, DIT_ATTN_ERR_KERNEL, "kernel must be -1 (automatic), 0 (128-row), 1 (ping-pong) or 2 (wide)");
+  ctx->force_kernel = kernel;
+  return DIT_ATTN_OK;
+}
+
 const char* dit_attn_last_error(const dit_attn_ctx* ctx) {
   return ctx ? ctx->error.c_str() : g_create_error.c_str();
 }
@@ -208,8 +217,10 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
   // Plan cache: the same pack comes back for every DiT block of every step.
   CachedPlan* plan = nullptr;
   const size_t cu_n = static_cast<size_t>(n_seqs) + 1;
+  const dit::AttnKernel kernel = ctx->force_kernel >= 0 ? static_cast<dit::AttnKernel>(ctx->force_kernel)
+                                                        : dit::attn_fwd_select(cu_seqlens, n_seqs, n_heads, ctx->n_cus);
   for (auto& p : ctx->plans) {
-    if (p->n_heads == n_heads && p->head_dim == head_dim && p->cu.size() == cu_n &&
+    if (p->n_heads == n_heads && p->head_dim == head_dim && p->kernel == kernel && p->cu.size() == cu_n &&
         std::memcmp(p->cu.data(), cu_seqlens, cu_n * sizeof(int32_t)) == 0) {
       plan = p.get();
       break;
@@ -222,7 +233,7 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
       np->cu.assign(cu_seqlens, cu_seqlens + cu_n);
       np->n_heads = n_heads;
       np->head_dim = head_dim;
-      np->kernel = dit::attn_fwd_select(cu_seqlens, n_seqs, n_heads, ctx->n_cus);
+      np->kernel = kernel;
       dit::plan_build(cu_seqlens, n_seqs, n_heads, dit::attn_fwd_block_m(np->kernel), np->host_items);
     } catch (...) {
       return fail(ctx, DIT_ATTN_ERR_HIP, "out of host memory while building the work-list");

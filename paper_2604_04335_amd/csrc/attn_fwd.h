@@ -22,11 +22,14 @@ struct AttnParams {
   int32_t negate;           // 1 when scale < 0: the sign of Q is flipped on load
 };
 
-// Two kernels share the tile code.
+// Three kernels share the tile code.
 //   kIndependent128: 4 wavefronts, 128 query rows per item, two unsynchronised workgroups per compute unit.
 //   kPingPong256:    8 wavefronts, 256 query rows per item, one workgroup per compute unit whose two wavefront
 //                    groups alternate between the matrix and the vector phase of consecutive tiles.
-enum class AttnKernel : int { kIndependent128 = 0, kPingPong256 = 1 };
+//   kWide256:        4 wavefronts of 64 query rows, 256 per item, one workgroup per compute unit; every K / V operand
+//                    read from LDS feeds two MFMAs and the softmax runs in the shadow of the wavefront's own MFMAs.
+//                    Does not take a negative scale (attn_fwd_launch runs the ping-pong kernel on the same work-list).
+enum class AttnKernel : int { kIndependent128 = 0, kPingPong256 = 1, kWide256 = 2 };
 
 // Which kernel a pack runs on a device with n_cus compute units (a pure function of the pack).
 AttnKernel attn_fwd_select(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int n_cus);
@@ -37,5 +40,8 @@ int attn_fwd_wgs_per_cu(AttnKernel kernel);
 
 // Enqueue the forward kernel with `grid` persistent workgroups.
 hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim, int grid, hipStream_t stream);
+
+// Defined with the wide kernel.
+hipError_t attn_fwd_wide_launch(const AttnParams& p, int head_dim, int grid, hipStream_t stream);
 
 }  // namespace dit

@@ -1,426 +1,8 @@
-// DiT denoising-step self-attention forward for gfx950 (MI355X).
-//
-// O[r,h,:] = sum_j softmax_j(scale * <Q[r,h,:], K[j,h,:]>) V[j,h,:], j over the
-// keys of r's own sequence (paper Sections 4.3 and 5 give the batch; the math is
-// plain softmax attention).  bf16 in, fp32 scores/state/accumulators, bf16 out.
-//
-// Mapping.  A persistent workgroup takes (sequence, head, query tile) items from
-// a list through one atomic counter.  Each wavefront owns 32 query rows.  K and V
-// tiles of BN keys are copied HBM -> LDS by direct (register-free) loads, double
-// buffered.  Both contractions run on the 32x32x16 bf16 MFMA in *transposed* form:
-//     S^T[key, query] = K[key, :] . Q[query, :]        A = K (from LDS), B = Q (registers)
-//     O^T[d,   query] += V^T[d, key] . P^T[key, query] A = V^T (LDS transpose read), B = P (registers)
-// In the MFMA result layout a lane holds one query column and 16 key rows, so the
-// row maximum and row sum of the online softmax are in-lane reductions plus one
-// exchange with lane^32, and the per-query rescale of O^T is a per-lane scalar.
-// The 16 probabilities a lane holds after the softmax are exactly the 2 x 8
-// k-slots of the B operand of the second contraction if the V^T operand uses the
-// same key order, which two 4-key transpose reads deliver.
-//
-// LDS layout.  A tile row is the ROW_B bytes of one key of one head, rows are
-// contiguous (a direct load writes 64 lanes x 16 B contiguously), and the 16-byte
-// chunks of a row are XOR-swizzled so that the 16 rows a b128 read touches per
-// pass (K) and the 4 rows x 64 B a transpose read touches per pass (V) fall in
-// distinct banks.  The swizzle is applied by choosing which global chunk a lane
-// fetches, so it costs nothing.
-//
-// O^T and the running sum are rescaled only in tiles where the maximum of some row of the wavefront
-// grows.  The reference maximum is always the true running maximum, so the largest probability of a
-// row is exactly 1 and is not perturbed by the bf16 rounding of P (a row dominated by one key then
-// returns that key's V row exactly; a stale reference would cost up to 2^-9 relative there).
-#include <hip/hip_runtime.h>
-#include <stdint.h>
-
-#include "attn_fwd.h"
+// DiT denoising-step self-attention forward for gfx950 (MI355X): the 128-row and the ping-pong kernel, and the launch
+// interface.  The tile code they share (and its description) is in attn_device.h.
+#include "attn_device.h"
 
 namespace dit {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
-typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
-
-typedef __attribute__((address_space(3))) char lds_char;
-typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
-typedef __attribute__((address_space(1))) const void gptr_void;
-
-// Operand reads of an MFMA stream run this many MFMAs ahead of their use.
-constexpr int kPrefetch = 4;
-// Full scheduling fence: the compiler's instruction scheduler moves nothing across it.
-#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-
-template <int D_, int NWAVES_, int BN_>
-struct Tile {
-  static constexpr int D = D_;
-  static constexpr int NWAVES = NWAVES_;
-  static constexpr int BN = BN_;
-  static constexpr int NT = NWAVES * 64;           // threads
-  static constexpr int BM = NWAVES * 32;           // query rows per workgroup
-  static constexpr int ROW_B = D * 2;              // bytes of one K/V row of one head
-  static constexpr int TILE_B = BN * ROW_B;        // one K or V tile in LDS
-  static constexpr int CPR = ROW_B / 16;           // 16-byte chunks per row
-  static constexpr int RPI = 64 / CPR;             // rows one direct-load instruction covers
-  static constexpr int GROUP = NWAVES * RPI;       // rows one round of loads (all waves) covers
-  static constexpr int LPT = BN / GROUP;           // load instructions per wave per tensor per tile
-  static constexpr int NKB = BN / 32;              // 32-key blocks per tile
-  static constexpr int NKS = D / 16;               // k-steps of the first contraction
-  static constexpr int NDB = D / 32;               // 32-wide d blocks of the output
-  static constexpr int NQK = NKB * NKS;            // MFMAs of S^T = K Q^T per tile
-  static constexpr int NPV = NKB * 2 * NDB;        // MFMAs of O^T += V^T P^T per tile
-  // LDS: [K0][K1][V0][V1][two item slots]
-  static constexpr int K_OFF = 0;
-  static constexpr int V_OFF = 2 * TILE_B;
-  static constexpr int ITEM_OFF = 4 * TILE_B;
-  static constexpr int LDS_BYTES = 4 * TILE_B + 16;
-  static_assert(GROUP % 16 == 0 && BN % GROUP == 0, "load rounds must keep row%16 fixed per lane");
-  static_assert(D == 64 || D == 128, "head dimension");
-
-  // Chunk swizzles (XOR on the 16-byte chunk index of a row).
-  //   K: the 16 consecutive rows of a b128 pass must land in 16 distinct 16-byte bank groups.
-  //   V: the 4 consecutive rows x 4 chunks of a transpose-read pass must land in 4 distinct 64-byte groups.
-  __device__ static constexpr int swz_k(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
-  __device__ static constexpr int swz_v(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
-};
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  f32x2 f = {a, b};
-  bf16x2 h = __builtin_convertvector(f, bf16x2);
-  return __builtin_bit_cast(uint32_t, h);
-}
-
-// Per-lane constants of a kernel instance.
-template <class T>
-struct Lane {
-  int lane, wave, l32, hh;
-  int lrow;               // row of this lane inside a GROUP-row load round
-  int kcol, vcol;         // byte column (swizzled chunk) this lane fetches for K / V
-  uint32_t kvoff, vvoff;  // lrow * row_stride + column, the 32-bit per-lane part of a load address
-
-  __device__ __forceinline__ void init(int tid, int64_t row_stride_b) {
-    lane = tid & 63;
-    wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    l32 = lane & 31;
-    hh = lane >> 5;
-    lrow = wave * T::RPI + lane / T::CPR;
-    kcol = ((lane % T::CPR) ^ T::swz_k(lrow)) * 16;
-    vcol = ((lane % T::CPR) ^ T::swz_v(lrow)) * 16;
-    kvoff = (uint32_t)lrow * (uint32_t)row_stride_b + (uint32_t)kcol;
-    vvoff = (uint32_t)lrow * (uint32_t)row_stride_b + (uint32_t)vcol;
-  }
-
-  // Operand addresses in the K / V buffers of parity 0 (recomputed per item: cheaper than keeping a second copy live).
-  //   ka[ks]: K operand chunk of k-step ks, 32-key block 0.   va[db]: V transpose read of d-block db, 16-key block 0.
-  // V^T operand: lane (d = 32*db + lane%32, half hh) needs keys {k0 .. k0+3} and {k0+8 .. k0+11},
-  // k0 = 32*kb + 16*u + 4*hh.  A transpose read returns, to lane i of a 16-lane group, element i%4 of
-  // the 8 bytes addressed by lanes i/4 + {0,4,8,12} of the group; so the lane addresses row k0 + (i16/4),
-  // columns 16*b + 4*(i16%4) .. +3 of the d-block and receives column 16*b + i16 of rows k0 .. k0+3.
-  __device__ __forceinline__ void operand_addrs(uint32_t lds_base, int (&ka)[T::NKS], int (&va)[T::NDB]) const {
-    const int i16 = lane & 15;
-    const int b = (lane >> 4) & 1;
-#pragma unroll
-    for (int ks = 0; ks < T::NKS; ++ks) ka[ks] = (int)lds_base + T::K_OFF + l32 * T::ROW_B + (((2 * ks + hh) ^ T::swz_k(l32)) * 16);
-    const int row = 4 * hh + (i16 >> 2);
-#pragma unroll
-    for (int db = 0; db < T::NDB; ++db) {
-      const int chunk = 4 * db + 2 * b + ((i16 & 3) >> 1);
-      va[db] = (int)lds_base + T::V_OFF + row * T::ROW_B + ((chunk ^ T::swz_v(row)) * 16) + 8 * (i16 & 1);
-    }
-  }
-};
-
-// Direct HBM -> LDS load of this wave's share of one K or V tile into the tile buffer at LDS byte offset dst_off.
-// base (start of the sequence's rows for this head), row_stride_b, key0 and kv_len are wave-uniform.  The address of a
-// lane is  scalar tile base + 32-bit lane offset;  in the last tile of a sequence rows past the end re-read the last
-// key (their scores are masked, and a finite V row times a zero probability adds nothing).
-// One direct-load instruction: 64 lanes x 16 bytes from (sbase + voff[lane]) to LDS bytes [lds_addr, lds_addr + 1024).
-// Written as inline assembly so that the compiler does not track it: it would otherwise make LDS reads that it
-// cannot prove disjoint wait for every outstanding direct load.  Completion is awaited explicitly (wait_loads).
-__device__ __forceinline__ void lds_dma_16(const char* sbase, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(voff), "s"(sbase)
-               : "memory");
-}
-
-template <class T>
-__device__ __forceinline__ void tile_load_one(const char* base, int64_t row_stride_b, int key0, int kv_len, int lrow,
-                                              int col, uint32_t voff, lds_char* smem, int dst_off, int wave) {
-  const char* tbase = base + (int64_t)key0 * row_stride_b;  // scalar
-  const uint32_t lds0 = (uint32_t)(uintptr_t)smem + (uint32_t)dst_off + (uint32_t)wave * 1024u;
-  if (key0 + T::BN <= kv_len) {
-#pragma unroll
-    for (int i = 0; i < T::LPT; ++i) {
-      const char* sbase = tbase + (int64_t)(i * T::GROUP) * row_stride_b;  // scalar
-      lds_dma_16(sbase, voff, lds0 + i * T::NWAVES * 1024);
-    }
-  } else {
-    const int last = kv_len - 1 - key0;  // >= 0
-#pragma unroll
-    for (int i = 0; i < T::LPT; ++i) {
-      int row = i * T::GROUP + lrow;
-      row = row < last ? row : last;
-      const uint32_t off = (uint32_t)row * (uint32_t)row_stride_b + (uint32_t)col;
-      lds_dma_16(tbase, off, lds0 + i * T::NWAVES * 1024);
-    }
-  }
-}
-
-template <int V>
-struct IC {
-  static constexpr int value = V;
-};
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(IC<I>{});
-    static_for<I + 1, N>(f);
-  }
-}
-
-// An MFMA stream: optionally O^T += V^T P^T (V tile addressed by va), then steps [Q0, Q1) of S^T = K Q^T (K tile
-// addressed by ka; step q is k-step q / NKB of key block q % NKB, and step 0 of a block starts it from zero).
-// Operand reads run PD MFMAs ahead of their use, through a ring of PD operand registers.
-template <class T, bool DO_PV, int Q0, int Q1, int PD>
-__device__ __forceinline__ void mfma_stream(lds_char* smem, const int (&va)[T::NDB], const int (&ka)[T::NKS],
-                                            const uint32_t (&pb)[T::NKB][8], const bf16x8 (&qf)[T::NKS],
-                                            f32x16 (&o)[T::NDB], f32x16 (&s)[T::NKB]) {
-  constexpr int NPV = DO_PV ? T::NPV : 0;
-  constexpr int NQK = Q1 - Q0;
-  constexpr int N = NPV + NQK;
-  static_assert(Q0 >= 0 && Q0 <= Q1 && Q1 <= T::NQK, "QK step range");
-  bf16x8 frag[PD];
-  int va_[T::NDB], ka_[T::NKS];
-#pragma unroll
-  for (int i = 0; i < T::NDB; ++i) va_[i] = va[i];
-#pragma unroll
-  for (int i = 0; i < T::NKS; ++i) ka_[i] = ka[i];
-
-  auto load_step = [&](auto jc) {
-    constexpr int J = decltype(jc)::value;
-    if constexpr (J < NPV) {  // PV step J: kb = J / (2*NDB), u = (J / NDB) % 2, db = J % NDB
-      constexpr int kb = J / (2 * T::NDB), u = (J / T::NDB) % 2, db = J % T::NDB;
-      lds_char* p0 = (lds_char*)(uintptr_t)(uint32_t)(va_[db] + (32 * kb + 16 * u) * T::ROW_B);
-      const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0));
-      const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * T::ROW_B));
-      frag[J % PD] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    } else {  // QK step: ks = q / NKB, kb = q % NKB (kb fastest: consecutive MFMAs use different accumulators)
-      constexpr int q = Q0 + J - NPV, ks = q / T::NKB, kb = q % T::NKB;
-      frag[J % PD] = *(lds_bf16x8*)(uintptr_t)(uint32_t)(ka_[ks] + kb * 32 * T::ROW_B);
-    }
-  };
-  auto mfma_step = [&](auto jc) {
-    constexpr int J = decltype(jc)::value;
-    if constexpr (J < NPV) {
-      constexpr int kb = J / (2 * T::NDB), u = (J / T::NDB) % 2, db = J % T::NDB;
-      u32x4 pw = {pb[kb][4 * u], pb[kb][4 * u + 1], pb[kb][4 * u + 2], pb[kb][4 * u + 3]};
-      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], __builtin_bit_cast(bf16x8, pw), o[db], 0, 0, 0);
-    } else {
-      constexpr int q = Q0 + J - NPV, ks = q / T::NKB, kb = q % T::NKB;
-      if constexpr (ks == 0) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], qf[ks], zero, 0, 0, 0);
-      } else {
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], qf[ks], s[kb], 0, 0, 0);
-      }
-    }
-  };
-
-  // Order.  The compiler is free to hoist LDS reads far above their MFMAs (it would then hold every operand of the
-  // stream in registers at once) and to reorder the two contractions.  An empty asm statement after each MFMA takes
-  // the accumulator just written as input and passes the address register of the next read through: the read cannot
-  // be issued before that MFMA, and volatile asm statements keep their order.  It emits no instruction.
-  auto tie = [&](auto jc) {
-    (void)s;
-    (void)o;
-    constexpr int J = decltype(jc)::value;   // MFMA just issued
-    constexpr int R = J + PD;                // read to issue next
-    if constexpr (R < N) {
-      if constexpr (J < NPV) {
-        constexpr int dbj = J % T::NDB;
-        if constexpr (R < NPV) {
-          asm volatile("" : "+v"(va_[R % T::NDB]) : "v"(o[dbj]));
-        } else {
-          asm volatile("" : "+v"(ka_[(Q0 + R - NPV) / T::NKB]) : "v"(o[dbj]));
-        }
-      } else {
-        constexpr int kbj = (Q0 + J - NPV) % T::NKB;
-        asm volatile("" : "+v"(ka_[(Q0 + R - NPV) / T::NKB]) : "v"(s[kbj]));
-      }
-    }
-  };
-  SCHED_FENCE();
-  static_for<0, (PD < N ? PD : N)>([&](auto jc) { load_step(jc); });
-  SCHED_FENCE();
-  static_for<0, N>([&](auto jc) {
-    constexpr int J = decltype(jc)::value;
-    mfma_step(jc);
-    tie(jc);
-    if constexpr (J + PD < N) load_step(IC<J + PD>{});
-    SCHED_FENCE();  // and the scheduler may not sink that read towards its use either
-  });
-  SCHED_FENCE();
-}
-
-// Online softmax of one tile: scores s -> bf16 probabilities pb (B-operand order), running max / sum, lazy rescale.
-// Element i of block kb is key 32*kb + 8*(i/4) + 4*hh + (i%4) of the tile, for query lane%32.
-template <class T, bool TAIL>
-__device__ __forceinline__ void tile_softmax(f32x16 (&s)[T::NKB], int hh, int keys_left, float c,
-                                             uint32_t (&pb)[T::NKB][8], f32x16 (&o)[T::NDB], float& m_ref,
-                                             float& l_run) {
-  if (TAIL) {
-#pragma unroll
-    for (int kb = 0; kb < T::NKB; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = 32 * kb + 8 * (i >> 2) + 4 * hh + (i & 3);
-        if (key >= keys_left) s[kb][i] = -__builtin_inff();
-      }
-  }
-
-  float mx = s[0][0];
-#pragma unroll
-  for (int kb = 0; kb < T::NKB; ++kb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) mx = __builtin_fmaxf(mx, s[kb][i]);
-  mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
-
-  // Rescale only if the running maximum of some row of this wave grew (rare after the first tiles).
-  const bool grow = mx > m_ref;
-  if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-    const float m_new = __builtin_fmaxf(m_ref, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);
-    m_ref = m_new;
-    l_run *= alpha;
-#pragma unroll
-    for (int db = 0; db < T::NDB; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-  }
-  const float mc = m_ref * c;
-
-  // Eight scores at a time, with a scheduling fence after each group: the probabilities are packed to bf16 and
-  // their fp32 values die before the next group starts, which keeps the register peak of this phase low.
-  float lsum = 0.f;
-#pragma unroll
-  for (int kb = 0; kb < T::NKB; ++kb) {
-#pragma unroll
-    for (int g = 0; g < 2; ++g) {
-#pragma unroll
-      for (int i = 8 * g; i < 8 * g + 8; i += 2) {
-        float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -mc));
-        float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i + 1], c, -mc));
-        if (TAIL) {
-          const int key = 32 * kb + 8 * (i >> 2) + 4 * hh + (i & 3);
-          if (key >= keys_left) p0 = 0.f;
-          if (key + 1 >= keys_left) p1 = 0.f;
-        }
-        lsum += p0 + p1;
-        pb[kb][i >> 1] = pack_bf16x2(p0, p1);
-      }
-      SCHED_FENCE();
-    }
-  }
-  l_run += lsum;
-}
-
-// All LDS accesses of this wave are complete, then workgroup barrier.  The "memory" clobber keeps the
-// compiler from moving LDS reads or direct loads across it.
-__device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-// Work distribution: thread 0 of a workgroup takes the next list index; indices at or past n_items end the workgroup.
-__device__ __forceinline__ uint32_t take_item(const AttnParams& p) { return atomicAdd(&p.sync[0], 1u); }
-// After the item loop: the last workgroup to get here clears both words for the next launch.
-__device__ __forceinline__ void finish_workgroup(const AttnParams& p) {
-  __threadfence();
-  const uint32_t done = atomicAdd(&p.sync[1], 1u);
-  if (done == gridDim.x - 1) {
-    p.sync[0] = 0u;
-    p.sync[1] = 0u;
-  }
-}
-
-// Work item fields, wave-uniform.
-struct ItemU {
-  int q_start, kv_start, kv_len, head, q_rows;
-};
-__device__ __forceinline__ ItemU fetch_item(const WorkItem* items, uint32_t idx) {
-  const WorkItem it = items[idx];
-  ItemU u;
-  u.q_start = __builtin_amdgcn_readfirstlane(it.q_start);
-  u.kv_start = __builtin_amdgcn_readfirstlane(it.kv_start);
-  u.kv_len = __builtin_amdgcn_readfirstlane(it.kv_len);
-  const int rh = __builtin_amdgcn_readfirstlane(it.rows_head);
-  u.head = rh & 0xFFFF;
-  u.q_rows = (rh >> 16) & 0xFFFF;
-  return u;
-}
-
-// Q fragments (B operand of S^T = K Q^T): lane holds query row l32 of its wave, d = 16*ks + 8*hh .. +7.
-template <class T>
-__device__ __forceinline__ void load_q(const AttnParams& p, const Lane<T>& L, const ItemU& it, int64_t row_stride_b,
-                                       int64_t head_off, int qrow, bf16x8 (&qf)[T::NKS]) {
-  const char* qptr = static_cast<const char*>(p.q) + (int64_t)(it.q_start + qrow) * row_stride_b + head_off + L.hh * 16;
-#pragma unroll
-  for (int ks = 0; ks < T::NKS; ++ks) {
-    u32x4 w = *reinterpret_cast<const u32x4*>(qptr + ks * 32);
-    if (p.negate) w ^= u32x4{0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
-    qf[ks] = __builtin_bit_cast(bf16x8, w);
-  }
-}
-
-// Epilogue: O^T / l -> bf16 -> out.  Lane holds d = 32*db + 8*g + 4*hh + j (i = 4*g + j) of query l32.
-template <class T>
-__device__ __forceinline__ void store_out(const AttnParams& p, const Lane<T>& L, const ItemU& it, int64_t row_stride_b,
-                                          int64_t head_off, int qrow, bool row_valid, const f32x16 (&o)[T::NDB],
-                                          float l_run) {
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (row_valid) {
-    const float inv = 1.0f / l_tot;
-    char* optr = static_cast<char*>(p.out) + (int64_t)(it.q_start + qrow) * row_stride_b + head_off + L.hh * 8;
-#pragma unroll
-    for (int db = 0; db < T::NDB; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 w;
-        w[0] = pack_bf16x2(o[db][4 * g + 0] * inv, o[db][4 * g + 1] * inv);
-        w[1] = pack_bf16x2(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
-        *reinterpret_cast<u32x2*>(optr + (32 * db + 8 * g) * 2) = w;
-      }
-  }
-}
-
-// Per-item state shared by both kernels.
-template <class T>
-struct ItemCtx {
-  ItemU it;
-  int nt;
-  int64_t head_off;
-  const char* kbase;
-  const char* vbase;
-  int qrow;
-  bool row_valid;
-};
-
-template <class T>
-__device__ __forceinline__ ItemCtx<T> begin_item(const AttnParams& p, const Lane<T>& L, uint32_t item_idx,
-                                                 int64_t row_stride_b) {
-  ItemCtx<T> c;
-  c.it = fetch_item(p.items, item_idx);
-  c.nt = (c.it.kv_len + T::BN - 1) / T::BN;
-  c.head_off = (int64_t)c.it.head * T::D * 2;
-  c.kbase = static_cast<const char*>(p.k) + (int64_t)c.it.kv_start * row_stride_b + c.head_off;
-  c.vbase = static_cast<const char*>(p.v) + (int64_t)c.it.kv_start * row_stride_b + c.head_off;
-  // Waves whose 32 rows lie past the end of a ragged query tile work on a copy of the last row and store nothing.
-  c.qrow = L.wave * 32 + L.l32;
-  c.row_valid = c.qrow < c.it.q_rows;
-  if (!c.row_valid) c.qrow = c.it.q_rows - 1;
-  return c;
-}
 
 // ---------------------------------------------------------------------------------------------
 // Kernel A: 4 wavefronts, 128 query rows per workgroup, two independent workgroups per compute unit.
@@ -455,8 +37,8 @@ attn_fwd_kernel(AttnParams p) {
     const int kv_len = X.it.kv_len, nt = X.nt;
 
     auto load_tile = [&](int ti) {  // K(ti), V(ti) -> buffers of parity ti&1
-      tile_load_one<T>(X.kbase, row_stride_b, ti * T::BN, kv_len, L.lrow, L.kcol, L.kvoff, smem, T::K_OFF + (ti & 1) * T::TILE_B, L.wave);
-      tile_load_one<T>(X.vbase, row_stride_b, ti * T::BN, kv_len, L.lrow, L.vcol, L.vvoff, smem, T::V_OFF + (ti & 1) * T::TILE_B, L.wave);
+      tile_load_one<T>(X.kbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, L.lrow, L.kcol, L.kvoff, smem, T::K_OFF + (ti & 1) * T::TILE_B, L.wave);
+      tile_load_one<T>(X.vbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, L.lrow, L.vcol, L.vvoff, smem, T::V_OFF + (ti & 1) * T::TILE_B, L.wave);
     };
     load_tile(0);
 
@@ -473,7 +55,7 @@ attn_fwd_kernel(AttnParams p) {
     f32x16 s[T::NKB];
     uint32_t pb[T::NKB][8];
     int ka[T::NKS], va[T::NDB];  // operand addresses in the buffers of the current tile's parity
-    L.operand_addrs((uint32_t)(uintptr_t)smem, ka, va);
+    L.operand_addrs((uint32_t)(uintptr_t)smem, (uint32_t)(uintptr_t)smem, ka, va);
 
     for (int t = 0; t < nt; ++t) {
       // Tile t has landed (this wave's loads), and after the barrier everyone's; everyone is also done
@@ -483,9 +65,9 @@ attn_fwd_kernel(AttnParams p) {
       if (t + 1 < nt) load_tile(t + 1);
       mfma_stream<T, false, 0, T::NQK, kPrefetch>(smem, va, ka, pb, qf, o, s);
       if (t + 1 < nt) {
-        tile_softmax<T, false>(s, L.hh, T::BN, c, pb, o, m_ref, l_run);
+        tile_softmax<T, false>(s, L.hh, TailRows{0, T::BN}, c, pb, o, m_ref, l_run);
       } else {
-        tile_softmax<T, true>(s, L.hh, kv_len - t * T::BN, c, pb, o, m_ref, l_run);
+        tile_softmax<T, true>(s, L.hh, tail_rows<T>(kv_len), c, pb, o, m_ref, l_run);
       }
       mfma_stream<T, true, 0, 0, kPrefetch>(smem, va, ka, pb, qf, o, s);
 #pragma unroll
@@ -546,10 +128,10 @@ attn_fwd_pp_kernel(AttnParams p) {
     const int kv_len = X.it.kv_len, nt = X.nt;
 
     auto load_k = [&](int ti) {  // K(ti) -> K buffer of parity ti&1
-      tile_load_one<T>(X.kbase, row_stride_b, ti * T::BN, kv_len, L.lrow, L.kcol, L.kvoff, smem, T::K_OFF + (ti & 1) * T::TILE_B, L.wave);
+      tile_load_one<T>(X.kbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, L.lrow, L.kcol, L.kvoff, smem, T::K_OFF + (ti & 1) * T::TILE_B, L.wave);
     };
     auto load_v = [&](int ti) {  // V(ti) -> V buffer of parity ti&1
-      tile_load_one<T>(X.vbase, row_stride_b, ti * T::BN, kv_len, L.lrow, L.vcol, L.vvoff, smem, T::V_OFF + (ti & 1) * T::TILE_B, L.wave);
+      tile_load_one<T>(X.vbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, L.lrow, L.vcol, L.vvoff, smem, T::V_OFF + (ti & 1) * T::TILE_B, L.wave);
     };
     auto load_pair = [&](int t) {  // what phases 2t+2 / 2t+3 read: K(t+1) and V(t)
       if (t + 1 < nt) load_k(t + 1);
@@ -563,8 +145,8 @@ attn_fwd_pp_kernel(AttnParams p) {
       const int w2 = L.wave - 4;
       const int lrow2 = L.lrow - 4 * T::RPI;
       const uint32_t d = (uint32_t)(4 * T::RPI) * (uint32_t)row_stride_b;
-      if (t + 1 < nt) tile_load_one<T>(X.kbase, row_stride_b, (t + 1) * T::BN, kv_len, lrow2, L.kcol, L.kvoff - d, smem, T::K_OFF + ((t + 1) & 1) * T::TILE_B, w2);
-      tile_load_one<T>(X.vbase, row_stride_b, t * T::BN, kv_len, lrow2, L.vcol, L.vvoff - d, smem, T::V_OFF + (t & 1) * T::TILE_B, w2);
+      if (t + 1 < nt) tile_load_one<T>(X.kbase, row_stride_b, tile_first_key<T>(t + 1, kv_len), kv_len, lrow2, L.kcol, L.kvoff - d, smem, T::K_OFF + ((t + 1) & 1) * T::TILE_B, w2);
+      tile_load_one<T>(X.vbase, row_stride_b, tile_first_key<T>(t, kv_len), kv_len, lrow2, L.vcol, L.vvoff - d, smem, T::V_OFF + (t & 1) * T::TILE_B, w2);
     };
     load_k(0);
     load_pair(0);
@@ -582,7 +164,7 @@ attn_fwd_pp_kernel(AttnParams p) {
     f32x16 s[T::NKB];
     uint32_t pb[T::NKB][8];
     int ka[T::NKS], va[T::NDB];  // ka: K buffer the next QK reads; va: V buffer the next PV reads
-    L.operand_addrs((uint32_t)(uintptr_t)smem, ka, va);
+    L.operand_addrs((uint32_t)(uintptr_t)smem, (uint32_t)(uintptr_t)smem, ka, va);
 
     wait_loads();
     wg_barrier();                  // K(0), K(1), V(0) of every wave have landed; phase 0 starts
@@ -595,7 +177,7 @@ attn_fwd_pp_kernel(AttnParams p) {
     for (int t = 0; t + 1 < nt; ++t) {
       // ---- vector phase: softmax(t), a full tile
       if (group == 1) load_pair_all(t + 1);
-      tile_softmax<T, false>(s, L.hh, T::BN, c, pb, o, m_ref, l_run);
+      tile_softmax<T, false>(s, L.hh, TailRows{0, T::BN}, c, pb, o, m_ref, l_run);
       wg_barrier();
       // ---- matrix phase: PV(t), QK(t+1)
       __builtin_amdgcn_s_setprio(1);
@@ -609,7 +191,7 @@ attn_fwd_pp_kernel(AttnParams p) {
       wg_barrier();
     }
     // ---- last tile: masked softmax, PV only
-    tile_softmax<T, true>(s, L.hh, kv_len - (nt - 1) * T::BN, c, pb, o, m_ref, l_run);
+    tile_softmax<T, true>(s, L.hh, tail_rows<T>(kv_len), c, pb, o, m_ref, l_run);
     wg_barrier();
     __builtin_amdgcn_s_setprio(1);
     mfma_stream<T, true, 0, 0, kPrefetch>(smem, va, ka, pb, qf, o, s);
@@ -637,19 +219,20 @@ static hipError_t launch_t(const AttnParams& p, int grid, hipStream_t stream) {
   return hipGetLastError();
 }
 
-int attn_fwd_block_m(AttnKernel kernel) { return kernel == AttnKernel::kPingPong256 ? 256 : 128; }
-int attn_fwd_wgs_per_cu(AttnKernel kernel) { return kernel == AttnKernel::kPingPong256 ? 1 : 2; }
+int attn_fwd_block_m(AttnKernel kernel) { return kernel == AttnKernel::kIndependent128 ? 128 : 256; }
+int attn_fwd_wgs_per_cu(AttnKernel kernel) { return kernel == AttnKernel::kIndependent128 ? 2 : 1; }
 
 AttnKernel attn_fwd_select(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int n_cus) {
-  // The ping-pong kernel needs at least one 256-row item per compute unit; smaller packs run the 128-row kernel,
-  // which cuts them into twice as many items.
+  // The 256-row kernels need at least one item per compute unit; smaller packs run the 128-row kernel, which cuts
+  // them into twice as many items.
   int64_t items256 = 0;
   for (int32_t i = 0; i < n_seqs; ++i) items256 += (int64_t)((cu_seqlens[i + 1] - cu_seqlens[i] + 255) / 256) * n_heads;
   return items256 >= n_cus ? AttnKernel::kPingPong256 : AttnKernel::kIndependent128;
 }
 
 hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim, int grid, hipStream_t stream) {
-  if (kernel == AttnKernel::kPingPong256) {
+  if (kernel == AttnKernel::kWide256 && !p.negate) return attn_fwd_wide_launch(p, head_dim, grid, stream);
+  if (kernel != AttnKernel::kIndependent128) {
     if (head_dim == 128) return launch_t<Tile<128, 8, 64>, attn_fwd_pp_kernel<Tile<128, 8, 64>>>(p, grid, stream);
     if (head_dim == 64) return launch_t<Tile<64, 8, 64>, attn_fwd_pp_kernel<Tile<64, 8, 64>>>(p, grid, stream);
   } else {

@@ -48,10 +48,16 @@ class Runner:
         assert bool((buf[GUARD_ROWS + T:] == SENTINEL).all()), "rows after out[T-1] were written"
         return out
 
-    def run(self, w, scale=None):
-        """w: dit_workloads.Workload.  Returns uint16 bits [T, H, D]."""
+    def run(self, w, scale=None, kernel=None):
+        """w: dit_workloads.Workload.  Returns uint16 bits [T, H, D].  kernel: one of da.KERNEL_* for this call only."""
         q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
-        out = self.run_dev(q, k, v, w.cu_seqlens, w.n_heads, w.head_dim, w.scale if scale is None else scale)
+        if kernel is not None:
+            da.dit_attn_set_kernel(self.ctx, kernel)
+        try:
+            out = self.run_dev(q, k, v, w.cu_seqlens, w.n_heads, w.head_dim, w.scale if scale is None else scale)
+        finally:
+            if kernel is not None:
+                da.dit_attn_set_kernel(self.ctx, da.KERNEL_AUTO)
         return to_bits(out)
 
 

@@ -148,6 +148,19 @@ def test_both_kernels_give_the_same_bits(runner):
     assert_parity(full[rows], ref, "ping-pong kernel, head_dim 64")
 
 
+@pytest.mark.parametrize("head_dim", [64, 128])
+def test_wide_kernel_gives_the_same_bits(runner, head_dim):
+    """The 64-rows-per-wavefront kernel against the ping-pong kernel on the same 256-row work-list: ragged tiles, a
+    one-tile and a two-tile sequence, an odd and an even number of tiles; and against the oracle."""
+    w = make_custom([1500, 64, 128, 1, 333, 2049], 3, head_dim, seed=31)
+    a = runner.run(w, kernel=da.KERNEL_PINGPONG)
+    b = runner.run(w, kernel=da.KERNEL_WIDE)
+    assert np.array_equal(a, b)
+    assert np.array_equal(runner.run(w, scale=-0.3, kernel=da.KERNEL_WIDE), runner.run(w, scale=-0.3, kernel=da.KERNEL_PINGPONG))
+    ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    assert_parity(b, ref, f"wide kernel, head_dim {head_dim}")
+
+
 def test_head_subset_equals_heads_of_wider_run(runner):
     """The head-split shard view: running heads [10, 20) alone equals those heads of a 40-head run."""
     w = make_custom([700], 40, 128, seed=22)
