@@ -173,26 +173,10 @@ __device__ __forceinline__ int tile_first_key(int ti, int kv_len) {
   return (key0 + T::BN > kv_len && kv_len >= T::BN) ? kv_len - T::BN : key0;
 }
 
-// Load instruction i (0 .. LPT-1) of this wave's share of the tile that starts at key0 = tile_first_key(..): rows
-// i*GROUP + lrow.  Rows past the end of a sequence shorter than a tile re-read its last key (their scores are masked,
-// and a finite V row times a zero probability adds nothing).
-template <class T>
-__device__ __forceinline__ void tile_load_part(const char* base, int64_t row_stride_b, int key0, int kv_len, int lrow,
-                                               int col, uint32_t voff, lds_char* smem, int dst_off, int wave, int i) {
-  const char* tbase = base + (int64_t)key0 * row_stride_b;  // scalar
-  const uint32_t lds0 = (uint32_t)(uintptr_t)smem + (uint32_t)dst_off + (uint32_t)wave * 1024u + (uint32_t)(i * T::NWAVES * 1024);
-  if (key0 + T::BN <= kv_len) {
-    const char* sbase = tbase + (int64_t)(i * T::GROUP) * row_stride_b;  // scalar
-    lds_dma_16(sbase, voff, lds0);
-  } else {
-    const int last = kv_len - 1 - key0;  // >= 0
-    int row = i * T::GROUP + lrow;
-    row = row < last ? row : last;
-    const uint32_t off = (uint32_t)row * (uint32_t)row_stride_b + (uint32_t)col;
-    lds_dma_16(tbase, off, lds0);
-  }
-}
-// The same for a tile that is known to be whole (every tile of a sequence of at least BN keys): no branch.
+// Rows past the end of a sequence shorter than a tile re-read its last key (their scores are masked, and a finite V
+// row times a zero probability adds nothing).
+// Load instruction i (0 .. LPT-1) of this wave's share of a tile that is known to be whole (every tile of a sequence
+// of at least BN keys): rows i*GROUP + lrow, no branch.
 template <class T>
 __device__ __forceinline__ void tile_load_part_whole(const char* base, int64_t row_stride_b, int key0, uint32_t voff,
                                                      lds_char* smem, int dst_off, int wave, int i) {
@@ -200,11 +184,28 @@ __device__ __forceinline__ void tile_load_part_whole(const char* base, int64_t r
   lds_dma_16(sbase, voff, (uint32_t)(uintptr_t)smem + (uint32_t)dst_off + (uint32_t)wave * 1024u + (uint32_t)(i * T::NWAVES * 1024));
 }
 
+// This wave's whole share of the tile that starts at key0 = tile_first_key(..): LPT instructions, one test.
 template <class T>
 __device__ __forceinline__ void tile_load_one(const char* base, int64_t row_stride_b, int key0, int kv_len, int lrow,
                                               int col, uint32_t voff, lds_char* smem, int dst_off, int wave) {
+  const char* tbase = base + (int64_t)key0 * row_stride_b;  // scalar
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem + (uint32_t)dst_off + (uint32_t)wave * 1024u;
+  if (key0 + T::BN <= kv_len) {
 #pragma unroll
-  for (int i = 0; i < T::LPT; ++i) tile_load_part<T>(base, row_stride_b, key0, kv_len, lrow, col, voff, smem, dst_off, wave, i);
+    for (int i = 0; i < T::LPT; ++i) {
+      const char* sbase = tbase + (int64_t)(i * T::GROUP) * row_stride_b;  // scalar
+      lds_dma_16(sbase, voff, lds0 + i * T::NWAVES * 1024);
+    }
+  } else {
+    const int last = kv_len - 1 - key0;  // >= 0
+#pragma unroll
+    for (int i = 0; i < T::LPT; ++i) {
+      int row = i * T::GROUP + lrow;
+      row = row < last ? row : last;
+      const uint32_t off = (uint32_t)row * (uint32_t)row_stride_b + (uint32_t)col;
+      lds_dma_16(tbase, off, lds0 + i * T::NWAVES * 1024);
+    }
+  }
 }
 
 template <int V>

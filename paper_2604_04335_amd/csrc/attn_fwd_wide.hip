@@ -25,7 +25,7 @@
 //
 // Arithmetic is the same, in the same order, as in the other kernels (a row's result does not depend on the kernel).
 // The row maximum of the last, partial tile is taken over all 64 score rows: the rows that are masked out of the sums
-// are copies of real keys of the same sequence (see tile_load_part), so the maximum over them is a maximum over real
+// are copies of real keys of the same sequence (see tile_first_key), so the maximum over them is a maximum over real
 // keys.
 #include "attn_device.h"
 
@@ -218,7 +218,7 @@ __device__ __forceinline__ void wide_stream(int (&va_)[T::NDB], int (&ka_)[T::NK
       });
       static_for<0, W::LPP>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
-        if constexpr (1 + 2 * i == J) issue_load(i);
+        if constexpr (1 + (NS / W::LPP) * i == J) issue_load(i);
       });
     }
   };
@@ -381,12 +381,22 @@ attn_fwd_wide_kernel(AttnParams p) {
     auto step = [&](f32x16 (&cur)[2][T::NKB], f32x16 (&nxt)[2][T::NKB], int t) {
       lsum[0] = 0.f;
       lsum[1] = 0.f;
-      auto issue = [&](int i) {  // load i of the pair L(t+3) = {K(t+4), V(t+3)}; nt >= 2 here, so every tile is whole
-        const bool is_k = i < T::LPT;
-        const int ti = is_k ? t + 4 : t + 3;
-        const int key0 = tile_first_key<T>(ti < nt ? ti : nt - 1, kv_len);
-        tile_load_part_whole<T>(is_k ? kbase : vbase, row_stride_b, key0, is_k ? L.kvoff : L.vvoff, smem,
-                                (is_k ? W::K_OFF : W::V_OFF) + (ti & 3) * T::TILE_B, L.wave, is_k ? i : i - T::LPT);
+      // Loads of the pair L(t+3) = {K(t+4), V(t+3)}; nt >= 2 here, so every tile is whole.  The tile addresses are
+      // formed once per step (scalar instructions also take issue slots of the one wavefront on this SIMD).
+      const int tk = t + 4 < nt ? t + 4 : nt - 1, tv = t + 3 < nt ? t + 3 : nt - 1;
+      const char* kptr = kbase + (int64_t)tile_first_key<T>(tk, kv_len) * row_stride_b;
+      const char* vptr = vbase + (int64_t)tile_first_key<T>(tv, kv_len) * row_stride_b;
+      const uint32_t kdst = (uint32_t)(uintptr_t)smem + W::K_OFF + ((t + 4) & 3) * T::TILE_B + L.wave * 1024;
+      const uint32_t vdst = (uint32_t)(uintptr_t)smem + W::V_OFF + ((t + 3) & 3) * T::TILE_B + L.wave * 1024;
+      const int64_t group_b = (int64_t)T::GROUP * row_stride_b;
+      auto issue = [&](int i) {
+        if (i < T::LPT) {
+          lds_dma_16(kptr, L.kvoff, kdst + i * T::NWAVES * 1024);
+          kptr += group_b;
+        } else {
+          lds_dma_16(vptr, L.vvoff, vdst + (i - T::LPT) * T::NWAVES * 1024);
+          vptr += group_b;
+        }
       };
       wide_stream<T, true, true, true, true, true>(va, ka, k_step(), ring, qf, o, cur, nxt, pb, mc, c, lsum, mx, issue);
       l_run[0] += lsum[0];
