@@ -30,9 +30,9 @@ DEFAULT_WORKLOAD = "mixed_varlen"
 # each scaled by what the same counter reads for the 1 GiB copy of --copy-calibration; the summaries and the
 # commands are under profiles/.  None where no such run has been made for the workload.
 MEASURED_HBM_BYTES = {
-    "mixed_varlen": 2_456_016_281,  # fetch 1047846.3 KiB x 2.000 + write 302760.8 KiB x 1.000
-    "sp_shard": 4_510_498_509,      # fetch 2103992.4 KiB x 2.000 + write 196798.9 KiB x 1.000
-    "t2v_single": 1_365_433_140,    # fetch 604196.2 KiB x 2.000 + write 125038.4 KiB x 1.000
+    "mixed_varlen": 3_116_608_921,  # fetch 1370972.8 KiB x 2.000 + write 301617.8 KiB x 1.000
+    "sp_shard": 6_828_207_718,      # fetch 3236122.4 KiB x 2.000 + write 195926.8 KiB x 1.000
+    "t2v_single": 1_609_594_880,    # fetch 721354.3 KiB x 2.000 + write 129161.4 KiB x 1.000
 }
 
 
@@ -140,6 +140,11 @@ def main():
     tflops = flops / (wall_ms * 1e-3) / 1e12
     kern_tflops = flops / (kern_ms * 1e-3) / 1e12
 
+    # Shader clock the chip sustained under the last timed launch (sampled inside the kernel, see include/dit_attn.h):
+    # MI355X lowers its clock under matrix load, so the share of the 2.4 GHz peak understates how busy the matrix pipe is.
+    clock_mhz, _ = da.dit_attn_last_launch_clock(ctx)
+    peak_at_clock = 256 * 4 * 1024 * clock_mhz * 1e6 / 1e12  # CUs x SIMDs x flop per cycle of the 32x32x16 bf16 MFMA
+
     _, block_m = da.dit_attn_plan(w.cu_seqlens, w.n_heads, w.head_dim)
     kernel_name = ("attn_fwd_pp_kernel<Tile<%d,8,64>>" if block_m == 256 else "attn_fwd_kernel<Tile<%d,4,64>>") % w.head_dim
 
@@ -178,6 +183,8 @@ def main():
             "traffic": MEASURED_HBM_BYTES.get(w.name),
             "kernel_ms_avg": round(kern_ms, 4),
             "algorithmic_hbm_bytes": int(4 * w.total_tokens * w.n_heads * w.head_dim * 2),
+            "shader_clock_mhz": round(clock_mhz, 1),
+            "frac_at_measured_clock": round(kern_tflops / peak_at_clock, 4) if peak_at_clock > 0 else None,
         },
     }
 

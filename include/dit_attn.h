@@ -119,6 +119,18 @@ void dit_attn_destroy(dit_attn_ctx* ctx);
 int dit_attn_set_kernel(dit_attn_ctx* ctx, int kernel);
 
 /*
+ * Clock sample of the last kernel launched through `ctx`: the first workgroup
+ * of every launch reads the GPU's shader-cycle counter and its constant 100 MHz
+ * counter when it starts and when it ends.  shader_mhz is the ratio (the clock
+ * the chip sustained under that kernel; MI355X lowers it under matrix load, so
+ * throughput at a fixed number of cycles per tile moves with it); kernel_ms is
+ * how long that workgroup ran.  Either pointer may be NULL; both values are 0
+ * before the first launch.  Synchronises the whole device.
+ * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL or DIT_ATTN_ERR_HIP.
+ */
+int dit_attn_last_launch_clock(dit_attn_ctx* ctx, double* shader_mhz, double* kernel_ms);
+
+/*
  * Text of the last error recorded in `ctx` (or of the last failed
  * dit_attn_create when ctx is NULL).  The string is owned by the library and
  * valid until the next call on the same context.

@@ -27,6 +27,7 @@ __all__ = [
     "dit_attn_last_error",
     "dit_attn_plan",
     "dit_attn_set_kernel",
+    "dit_attn_last_launch_clock",
     "KERNEL_AUTO",
     "KERNEL_128",
     "KERNEL_PINGPONG",
@@ -84,6 +85,8 @@ def load_library() -> ctypes.CDLL:
     lib.dit_attn_last_error.argtypes = [vp]
     lib.dit_attn_set_kernel.restype = ctypes.c_int
     lib.dit_attn_set_kernel.argtypes = [vp, ctypes.c_int]
+    lib.dit_attn_last_launch_clock.restype = ctypes.c_int
+    lib.dit_attn_last_launch_clock.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.dit_attn_plan.restype = i64
     lib.dit_attn_plan.argtypes = [i32p, i32, i32, i32, i32p, i64, i32p]
     _LIB = lib
@@ -132,6 +135,15 @@ def dit_attn_set_kernel(ctx, kernel: int) -> None:
     rc = load_library().dit_attn_set_kernel(ctypes.c_void_p(ctx), int(kernel))
     if rc != 0:
         raise DitAttnError(rc, dit_attn_last_error(ctx))
+
+
+def dit_attn_last_launch_clock(ctx):
+    """(shader clock in MHz, milliseconds) sampled by the first workgroup of the last launch; synchronises the device."""
+    mhz, ms = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    rc = load_library().dit_attn_last_launch_clock(ctypes.c_void_p(ctx), ctypes.byref(mhz), ctypes.byref(ms))
+    if rc != 0:
+        raise DitAttnError(rc, dit_attn_last_error(ctx))
+    return mhz.value, ms.value
 
 
 def dit_attn_destroy(ctx) -> None:

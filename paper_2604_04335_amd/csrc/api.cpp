@@ -37,7 +37,7 @@ thread_local std::string g_create_error;
 struct dit_attn_ctx {
   int device = 0;
   int n_cus = 0;
-  uint32_t* sync = nullptr;     // device, 2 words: items taken, workgroups finished; zero between launches
+  uint32_t* sync = nullptr;     // device, 8 words: work counters (zero between launches) and the last launch's clock sample
   uint64_t tick = 0;
   int force_kernel = -1;        // -1: chosen per pack; else a dit::AttnKernel value (dit_attn_set_kernel)
   std::vector<std::unique_ptr<CachedPlan>> plans;
@@ -134,8 +134,8 @@ int dit_attn_create(dit_attn_ctx** out_ctx, int device_id) {
   ctx->n_cus = prop.multiProcessorCount;
   DeviceGuard guard;
   e = guard.enter(device_id);
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->sync), 2 * sizeof(uint32_t));
-  if (e == hipSuccess) e = hipMemset(ctx->sync, 0, 2 * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->sync), 8 * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMemset(ctx->sync, 0, 8 * sizeof(uint32_t));
   if (e != hipSuccess) {
     (void)hipGetLastError();
     g_create_error = std::string("context set-up: ") + hipGetErrorString(e);
@@ -164,6 +164,22 @@ int dit_attn_set_kernel(dit_attn_ctx* ctx, int kernel) {
   if (kernel < -1 || kernel > static_cast<int>(dit::AttnKernel::kWide256))
     return fail(ctx, DIT_ATTN_ERR_KERNEL, "kernel must be -1 (automatic), 0 (128-row), 1 (ping-pong) or 2 (wide)");
   ctx->force_kernel = kernel;
+  return DIT_ATTN_OK;
+}
+
+int dit_attn_last_launch_clock(dit_attn_ctx* ctx, double* shader_mhz, double* kernel_ms) {
+  if (!ctx) return DIT_ATTN_ERR_NULL;
+  DeviceGuard guard;
+  hipError_t e = guard.enter(ctx->device);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+  e = hipDeviceSynchronize();
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipDeviceSynchronize");
+  uint64_t sample[2] = {0, 0};
+  e = hipMemcpy(sample, ctx->sync + 2, sizeof(sample), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpy(clock sample)");
+  const double ticks = static_cast<double>(sample[1]);
+  if (shader_mhz) *shader_mhz = ticks > 0 ? 100.0 * static_cast<double>(sample[0]) / ticks : 0.0;
+  if (kernel_ms) *kernel_ms = ticks * 1e-5;
   return DIT_ATTN_OK;
 }
 

@@ -389,6 +389,26 @@ __device__ __forceinline__ void finish_workgroup(const AttnParams& p) {
   }
 }
 
+// Clock sample of a launch: workgroup 0 (persistent, so it lives about as long as the kernel) reads the shader-cycle
+// counter and the constant 100 MHz counter when it starts and when it ends, and leaves the two differences in
+// sync[2..5].  Their ratio is the shader clock the chip sustained under this kernel.
+struct LaunchClock {
+  uint64_t cycles, ticks;
+};
+__device__ __forceinline__ LaunchClock launch_clock_begin() {
+  LaunchClock c;
+  c.cycles = __builtin_readcyclecounter();
+  c.ticks = __builtin_amdgcn_s_memrealtime();
+  return c;
+}
+__device__ __forceinline__ void launch_clock_end(const AttnParams& p, const LaunchClock& c0) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    uint64_t* out = reinterpret_cast<uint64_t*>(p.sync + 2);
+    out[0] = __builtin_readcyclecounter() - c0.cycles;
+    out[1] = __builtin_amdgcn_s_memrealtime() - c0.ticks;
+  }
+}
+
 // Work item fields, wave-uniform.
 struct ItemU {
   int q_start, kv_start, kv_len, head, q_rows;

@@ -13,7 +13,9 @@ struct AttnParams {
   const void* v;
   void* out;                // bf16 [T, H, D]
   const WorkItem* items;    // device work-list
-  uint32_t* sync;           // device, 2 words: [0] items taken so far, [1] workgroups finished.  Both are zero
+  uint32_t* sync;           // device, 8 words (8-byte aligned): [0] items taken so far, [1] workgroups finished,
+                            // [2..3] shader cycles and [4..5] 100 MHz ticks workgroup 0 of the last launch ran for.
+                            // Words 0 and 1 are zero
                             // between launches: the last workgroup to finish clears them (so a launch can be
                             // replayed from a captured graph, and the host keeps no count).
   uint32_t n_items;

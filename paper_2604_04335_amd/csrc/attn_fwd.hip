@@ -16,6 +16,7 @@ attn_fwd_kernel(AttnParams p) {
   lds_char* smem = (lds_char*)smem_generic;
   volatile uint32_t* s_item = reinterpret_cast<volatile uint32_t*>(smem_generic + T::ITEM_OFF);
 
+  const LaunchClock clock0 = launch_clock_begin();
   const int tid = threadIdx.x;
   const int64_t row_stride_b = (int64_t)p.n_heads * T::D * 2;
   const float c = p.c_log2;
@@ -79,6 +80,7 @@ attn_fwd_kernel(AttnParams p) {
     store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run);
     wg_barrier();  // the next item's first loads overwrite the buffers of parity 0
   }
+  launch_clock_end(p, clock0);
   if (tid == 0) finish_workgroup(p);
 }
 
@@ -106,6 +108,7 @@ attn_fwd_pp_kernel(AttnParams p) {
   lds_char* smem = (lds_char*)smem_generic;
   volatile uint32_t* s_item = reinterpret_cast<volatile uint32_t*>(smem_generic + T::ITEM_OFF);
 
+  const LaunchClock clock0 = launch_clock_begin();
   const int tid = threadIdx.x;
   const int64_t row_stride_b = (int64_t)p.n_heads * T::D * 2;
   const float c = p.c_log2;
@@ -201,6 +204,7 @@ attn_fwd_pp_kernel(AttnParams p) {
     store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run);
     if (group == 0) wg_barrier();  // group 0 idles (after its stores) while group 1 runs its last matrix phase
   }
+  launch_clock_end(p, clock0);
   if (tid == 0) finish_workgroup(p);
 }
 

@@ -253,6 +253,7 @@ attn_fwd_wide_kernel(AttnParams p) {
   lds_char* smem = (lds_char*)smem_generic;
   volatile uint32_t* s_item = reinterpret_cast<volatile uint32_t*>(smem_generic + W::ITEM_OFF);
 
+  const LaunchClock clock0 = launch_clock_begin();
   const int tid = threadIdx.x;
   const int64_t row_stride_b = (int64_t)p.n_heads * T::D * 2;
   const float c = p.c_log2;
@@ -458,6 +459,7 @@ attn_fwd_wide_kernel(AttnParams p) {
       SCHED_FENCE();
     }
   }
+  launch_clock_end(p, clock0);
   if (tid == 0) finish_workgroup(p);
 }
 

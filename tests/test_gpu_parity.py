@@ -161,6 +161,15 @@ def test_wide_kernel_gives_the_same_bits(runner, head_dim):
     assert_parity(b, ref, f"wide kernel, head_dim {head_dim}")
 
 
+def test_launch_clock_sample(runner):
+    """The clock sample of the last launch: a plausible shader clock (MI355X runs at 2.4 GHz at most) and a duration."""
+    w = make_custom([2048], 8, 128, seed=33)
+    runner.run(w)
+    mhz, ms = da.dit_attn_last_launch_clock(runner.ctx)
+    assert 300.0 < mhz < 2600.0, mhz
+    assert 0.0 < ms < 1000.0, ms
+
+
 def test_head_subset_equals_heads_of_wider_run(runner):
     """The head-split shard view: running heads [10, 20) alone equals those heads of a 40-head run."""
     w = make_custom([700], 40, 128, seed=22)
