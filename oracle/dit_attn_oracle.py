@@ -34,6 +34,23 @@ returning V, key-permutation invariance and query-permutation equivariance,
 key-shift invariance, scale = 0 giving the mean of V, the convex-hull bound,
 the hard-max limit, pack isolation, head independence, and agreement with
 torch's CPU scaled_dot_product_attention in float64.
+
+Further definitions (same status: test infrastructure), each pinned in the same file:
+
+  * the row-wise log-sum-exp  lse[r,h] = log sum_j exp(s_j)  (natural log) that goes with O.  It is what makes
+    partial results over disjoint key sets combinable, which sequence parallelism along the sequence (the ring half
+    of the unified sequence parallelism of Section 5) needs.  Pins: scipy's logsumexp on explicit logits, the
+    identical-keys and one-key closed forms, a hand case with logits ln 2 and ln 3.
+  * merge_partials: given P results (O_p, lse_p) of the same queries over disjoint key sets,
+        lse = log sum_p exp(lse_p),   O = sum_p exp(lse_p - lse) O_p,
+    which is the attention over the union (a softmax over a union of sets is the lse-weighted mixture of the softmaxes
+    over the sets).  Pins: attention over the union computed directly, a pure-Python loop, order invariance, a part
+    with no keys, identical parts.
+  * attention_cross_varlen: queries and keys with separate sequence boundaries (Section 2.1: DiT blocks also
+    cross-attend to the text tokens; sequence i's queries cu_q[i]:cu_q[i+1] see keys cu_k[i]:cu_k[i+1]).  Reading:
+    a sequence without keys gives O = 0 and lse = -inf (an empty sum).  Pins: equals the self-attention oracle when the
+    boundaries coincide, a pure-Python loop with Lq != Lk, torch's CPU attention in float64 with Lq != Lk, key
+    permutation invariance, pack isolation.
 """
 from __future__ import annotations
 
@@ -45,6 +62,10 @@ __all__ = [
     "attention_single",
     "attention_varlen",
     "attention_varlen_rows",
+    "logsumexp_scores",
+    "attention_varlen_lse",
+    "attention_cross_varlen",
+    "merge_partials",
 ]
 
 
@@ -124,3 +145,65 @@ def attention_varlen_rows(q, k, v, cu_seqlens, scale: float, rows) -> np.ndarray
             vh = _as_f64(v[s:e, h, :])
             out[lo:hi, h, :] = attention_single(qh, kh, vh, scale)
     return out
+
+
+def logsumexp_scores(q: np.ndarray, k: np.ndarray, scale: float) -> np.ndarray:
+    """lse[r] = log sum_j exp(scale * <q_r, k_j>) for one sequence and one head, float64; -inf where k has no rows."""
+    if k.shape[0] == 0:
+        return np.full(q.shape[0], -np.inf)
+    s = scale * (q @ k.T)
+    m = s.max(axis=1)
+    return m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+
+
+def attention_cross_varlen(q, k, v, cu_seqlens_q, cu_seqlens_k, scale: float, row_chunk: int = 2048):
+    """Attention with separate query and key boundaries.  q: [Tq, H, D]; k, v: [Tk, H, D].
+
+    Sequence i: query rows cu_seqlens_q[i]:cu_seqlens_q[i+1] attend to key rows cu_seqlens_k[i]:cu_seqlens_k[i+1].
+    Returns (O float64 [Tq, H, D], lse float64 [Tq, H]).  A sequence without keys: O = 0, lse = -inf.
+    """
+    cq = np.asarray(cu_seqlens_q, dtype=np.int64)
+    ck = np.asarray(cu_seqlens_k, dtype=np.int64)
+    Tq, H, D = q.shape
+    assert len(cq) == len(ck) and int(cq[0]) == 0 and int(ck[0]) == 0
+    assert int(cq[-1]) == Tq and int(ck[-1]) == k.shape[0] == v.shape[0]
+    assert np.all(np.diff(cq) >= 0) and np.all(np.diff(ck) >= 0)
+    out = np.zeros((Tq, H, D), dtype=np.float64)
+    lse = np.full((Tq, H), -np.inf, dtype=np.float64)
+    for i in range(len(cq) - 1):
+        qs, qe, ks, ke = int(cq[i]), int(cq[i + 1]), int(ck[i]), int(ck[i + 1])
+        if qe == qs or ke == ks:
+            continue
+        for h in range(H):
+            qh = _as_f64(q[qs:qe, h, :])
+            kh = _as_f64(k[ks:ke, h, :])
+            vh = _as_f64(v[ks:ke, h, :])
+            for r0 in range(0, qe - qs, row_chunk):
+                r1 = min(qe - qs, r0 + row_chunk)
+                out[qs + r0:qs + r1, h, :] = attention_single(qh[r0:r1], kh, vh, scale)
+                lse[qs + r0:qs + r1, h] = logsumexp_scores(qh[r0:r1], kh, scale)
+    return out, lse
+
+
+def attention_varlen_lse(q, k, v, cu_seqlens, scale: float, row_chunk: int = 2048):
+    """(O, lse) of the self-attention over a packed batch: attention_varlen plus the row-wise log-sum-exp [T, H]."""
+    return attention_cross_varlen(q, k, v, cu_seqlens, cu_seqlens, scale, row_chunk)
+
+
+def merge_partials(o_parts, lse_parts):
+    """Combine P partial results over disjoint key sets.  o_parts: [P, T, H, D]; lse_parts: [P, T, H]; float64.
+
+    Returns (O [T, H, D], lse [T, H]).  A part whose lse is -inf (no keys) has weight 0; if every part of a row is
+    -inf the row is 0 with lse -inf.
+    """
+    o = np.asarray(o_parts, dtype=np.float64)
+    l = np.asarray(lse_parts, dtype=np.float64)
+    assert o.ndim == 4 and l.shape == o.shape[:3]
+    m = l.max(axis=0)
+    m_safe = np.where(np.isfinite(m), m, 0.0)
+    e = np.exp(l - m_safe[None])          # exp(-inf) = 0
+    tot = e.sum(axis=0)
+    with np.errstate(divide="ignore"):
+        lse = m_safe + np.log(tot)        # log(0) = -inf
+    w = np.divide(e, tot[None], out=np.zeros_like(e), where=tot[None] > 0)
+    return (w[..., None] * o).sum(axis=0), lse

@@ -308,3 +308,145 @@ def test_sample_rows_properties():
             assert np.any((rows >= b) & (rows < min(e, b + 64)))
     few = sample_rows(cu, seed=1, block=64, max_rows=30)
     assert len(few) <= 30 and 999 in few
+
+
+# ---------------------------------------------------------------- log-sum-exp, merge of partial results, cross-attention
+
+GOLDEN_LSE = os.path.join(os.path.dirname(__file__), "golden", "lse_merge_cases.txt")
+
+
+def _lse_merge_cases(kind):
+    env = {"ln2": math.log(2), "ln3": math.log(3), "ln4": math.log(4), "ln5": math.log(5), "ln8": math.log(8)}
+    ev = lambda e: eval(e, {"__builtins__": {}}, env)  # noqa: E731
+    vec = lambda t: np.array([ev(x) for x in t.split(";")], dtype=np.float64)  # noqa: E731
+    cases = []
+    with open(GOLDEN_LSE) as f:
+        for line in f:
+            parts = [p.strip() for p in line.strip().split("|")]
+            if not line.strip() or line.startswith("#") or parts[0] != kind:
+                continue
+            cases.append(parts[1:] if kind == "lse" else parts[1:])
+    return cases, ev, vec
+
+
+def test_lse_hand_cases():
+    cases, ev, vec = _lse_merge_cases("lse")
+    assert len(cases) >= 2
+    for name, scale, q, k, want in cases:
+        qa = np.array([[ev(q)]]); ka = vec(k)[:, None]
+        got = orc.logsumexp_scores(qa, ka, float(scale))
+        assert abs(got[0] - ev(want)) < 1e-14, name
+
+
+def test_merge_hand_cases():
+    cases, ev, vec = _lse_merge_cases("merge")
+    assert len(cases) >= 2
+    for name, lses, os_, want_lse, want_o in cases:
+        l = vec(lses)[:, None, None]
+        o = vec(os_)[:, None, None, None]
+        got_o, got_l = orc.merge_partials(o, l)
+        assert abs(got_l[0, 0] - ev(want_lse)) < 1e-14 and abs(got_o[0, 0, 0] - ev(want_o)) < 1e-14, name
+
+
+def test_lse_against_scipy_and_closed_forms():
+    from scipy.special import logsumexp
+    q, k = _rand((7, 16), 301), _rand((13, 16), 302)
+    for scale in (0.25, -0.7, 0.0):
+        want = logsumexp(scale * np.einsum("rd,jd->rj", q, k), axis=1)
+        assert np.allclose(orc.logsumexp_scores(q, k, scale), want, rtol=0, atol=1e-13)
+    # identical keys: lse = scale <q, k> + ln L; one key: lse = scale <q, k>; huge logits do not overflow
+    k1 = np.repeat(_rand((1, 16), 303), 9, axis=0)
+    assert np.allclose(orc.logsumexp_scores(q, k1, 0.3), 0.3 * (q @ k1[0]) + math.log(9), atol=1e-13)
+    assert np.allclose(orc.logsumexp_scores(q, k1[:1], 0.3), 0.3 * (q @ k1[0]), atol=1e-13)
+    big = orc.logsumexp_scores(1e3 * q, 1e3 * k, 1.0)
+    assert np.all(np.isfinite(big)) and np.allclose(big, (1e6 * (q @ k.T)).max(axis=1), rtol=1e-12)
+    assert np.all(orc.logsumexp_scores(q, k[:0], 1.0) == -np.inf)
+
+
+def test_varlen_lse_layout_and_o_unchanged():
+    w = make_custom([5, 1, 9], 2, 8, seed=304)
+    o, lse = orc.attention_varlen_lse(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    assert np.array_equal(o, orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale))
+    qf, kf = orc.widen_bf16(w.q), orc.widen_bf16(w.k)
+    for (s, e) in ((0, 5), (5, 6), (6, 15)):
+        for h in range(2):
+            for r in range(s, e):
+                want = math.log(sum(math.exp(w.scale * float(qf[r, h] @ kf[j, h])) for j in range(s, e)))
+                assert abs(lse[r, h] - want) < 1e-12
+
+
+@pytest.mark.parametrize("splits", [(4, 9), (1, 2, 12), (13,)])
+def test_merge_of_disjoint_key_sets_is_attention_over_the_union(splits):
+    """The identity the merge rests on, against the (separately pinned) attention definition."""
+    L, D, scale = 13, 8, 0.4
+    q, k, v = _rand((6, D), 305), _rand((L, D), 306), _rand((L, D), 307)
+    perm = np.random.Generator(np.random.PCG64(308)).permutation(L)   # parts need not be contiguous ranges
+    bounds = [0] + list(splits) + ([L] if splits[-1] != L else [])
+    o_parts, l_parts = [], []
+    for a, b in zip(bounds[:-1], bounds[1:]):
+        idx = perm[a:b]
+        o_parts.append(orc.attention_single(q, k[idx], v[idx], scale)[:, None, :])
+        l_parts.append(orc.logsumexp_scores(q, k[idx], scale)[:, None])
+    o, lse = orc.merge_partials(np.stack(o_parts), np.stack(l_parts))
+    assert np.allclose(o[:, 0], orc.attention_single(q, k, v, scale), rtol=0, atol=1e-13)
+    assert np.allclose(lse[:, 0], orc.logsumexp_scores(q, k, scale), rtol=0, atol=1e-13)
+    # order of the parts does not matter; a part without keys changes nothing
+    o2, lse2 = orc.merge_partials(np.stack(o_parts[::-1] + [np.full_like(o_parts[0], 7.0)]),
+                                  np.stack(l_parts[::-1] + [np.full_like(l_parts[0], -np.inf)]))
+    assert np.allclose(o2, o, atol=1e-13) and np.allclose(lse2, lse, atol=1e-13)
+
+
+def test_merge_brute_force_and_degenerate_rows():
+    g = np.random.Generator(np.random.PCG64(309))
+    P, T, H, D = 3, 4, 2, 3
+    o, l = g.standard_normal((P, T, H, D)), 3.0 * g.standard_normal((P, T, H))
+    got_o, got_l = orc.merge_partials(o, l)
+    for t in range(T):
+        for h in range(H):
+            z = sum(math.exp(l[p, t, h]) for p in range(P))
+            assert abs(got_l[t, h] - math.log(z)) < 1e-12
+            for d in range(D):
+                assert abs(got_o[t, h, d] - sum(math.exp(l[p, t, h]) * o[p, t, h, d] for p in range(P)) / z) < 1e-12
+    # identical parts give that part (weights sum to one); a row whose parts are all empty is zero with lse -inf
+    same, ls = np.repeat(o[:1], 3, axis=0), l.copy()
+    assert np.allclose(orc.merge_partials(same, ls)[0], o[0], atol=1e-13)
+    ls[:, 1, 0] = -np.inf
+    zo, zl = orc.merge_partials(o, ls)
+    assert np.all(zo[1, 0] == 0.0) and zl[1, 0] == -np.inf and np.all(np.isfinite(zo))
+
+
+def test_cross_attention_equals_self_attention_on_equal_boundaries_and_brute_force():
+    w = make_custom([6, 3, 10], 2, 8, seed=310)
+    o, _ = orc.attention_cross_varlen(w.q, w.k, w.v, w.cu_seqlens, w.cu_seqlens, w.scale)
+    assert np.array_equal(o, orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale))
+    # different query and key lengths, a sequence without keys, one without queries
+    cq, ck = np.array([0, 4, 6, 6, 9]), np.array([0, 7, 7, 9, 14])
+    q, k, v = _rand((9, 2, 4), 311), _rand((14, 2, 4), 312), _rand((14, 2, 4), 313)
+    o, lse = orc.attention_cross_varlen(q, k, v, cq, ck, 0.6)
+    for i in range(4):
+        for r in range(cq[i], cq[i + 1]):
+            for h in range(2):
+                keys = range(ck[i], ck[i + 1])
+                if len(keys) == 0:
+                    assert np.all(o[r, h] == 0.0) and lse[r, h] == -np.inf
+                    continue
+                wts = [math.exp(0.6 * float(q[r, h] @ k[j, h])) for j in keys]
+                z = sum(wts)
+                want = sum(wj * v[j, h] for wj, j in zip(wts, keys)) / z
+                assert np.allclose(o[r, h], want, atol=1e-13) and abs(lse[r, h] - math.log(z)) < 1e-12
+
+
+def test_cross_attention_against_torch_and_invariances():
+    Lq, Lk, H, D = 5, 11, 3, 16
+    q, k, v = _rand((Lq, H, D), 314), _rand((Lk, H, D), 315), _rand((Lk, H, D), 316)
+    o, _ = orc.attention_cross_varlen(q, k, v, [0, Lq], [0, Lk], 0.37)
+    tq, tk, tv = (torch.from_numpy(x).permute(1, 0, 2)[None] for x in (q, k, v))
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=0.37)[0].permute(1, 0, 2).numpy()
+    assert np.allclose(o, want, atol=1e-12)
+    perm = np.random.Generator(np.random.PCG64(317)).permutation(Lk)
+    assert np.allclose(orc.attention_cross_varlen(q, k[perm], v[perm], [0, Lq], [0, Lk], 0.37)[0], o, atol=1e-13)
+    assert not np.allclose(orc.attention_cross_varlen(q, k[perm], v, [0, Lq], [0, Lk], 0.37)[0], o, atol=1e-3)
+    # pack isolation: a second sequence's keys do not reach the first sequence's queries
+    q2, k2, v2 = np.concatenate([q, q[:2]]), np.concatenate([k, _rand((4, H, D), 318)]), np.concatenate([v, _rand((4, H, D), 319)])
+    o2, _ = orc.attention_cross_varlen(q2, k2, v2, [0, Lq, Lq + 2], [0, Lk, Lk + 4], 0.37)
+    assert np.array_equal(o2[:Lq], o)
