@@ -99,6 +99,61 @@ def cpu_baseline(w, budget_s: float = 40.0):
     }
 
 
+HBM_PEAK_GBS = 8000.0
+
+
+def _time_calls(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    for i in range(steps):
+        starts[i].record()
+        fn()
+        ends[i].record()
+    torch.cuda.synchronize()
+    return float(np.mean([s.elapsed_time(e) for s, e in zip(starts, ends)]))
+
+
+def bench_other(da, torch, ctx, args):
+    """Lines for the two operations built around the headline path (not the driver's metric)."""
+    stream = torch.cuda.current_stream().cuda_stream
+    H, D = 24, 128
+    if args.op == "merge":
+        # rows of mixed_varlen, four partial results (a 4-way split of the keys)
+        T, P = 49178, 4
+        g = torch.Generator(device="cuda").manual_seed(7)
+        parts = [torch.randn((T, H, D), device="cuda", generator=g).to(torch.bfloat16) for _ in range(P)]
+        lses = [torch.randn((T, H), device="cuda", generator=g) * 3 for _ in range(P)]
+        out = torch.empty_like(parts[0])
+        lse = torch.empty_like(lses[0])
+        ms = _time_calls(torch, lambda: da.dit_attn_merge(ctx, parts, lses, T, H, D, out, lse, stream), args.steps, args.warmup)
+        nbytes = (P + 1) * (T * H * D * 2 + T * H * 4)
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        return {"metric": "partial-result merge, GB/s of algorithmic HBM traffic, 1 GPU", "value": round(gbs, 1), "unit": "GB/s",
+                "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+                "dtype": "bf16", "data": "synthetic", "config": {"workload": "merge of 4 parts, 49178 rows x 24 heads x 128"},
+                "roofline": {"bound": "hbm", "kernel": "merge_kernel<4>", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_hbm_bytes": nbytes}}
+    from dit_workloads import make_cross
+    q_lens, k_lens = [4352] * 6 + [20506], [512] * 7   # latent queries of six images and one video against 512 text keys
+    w = make_cross(q_lens, k_lens, H, D, seed=2001)
+    q, k, v = _to_dev(w.q, torch), _to_dev(w.k, torch), _to_dev(w.v, torch)
+    out = torch.empty_like(q)
+    ms = _time_calls(torch, lambda: da.dit_attn_cross_varlen_fwd(ctx, q, k, v, w.cu_seqlens_q, w.cu_seqlens_k, H, D, w.scale, out,
+                                                               None, stream), args.steps, args.warmup)
+    flops = 4.0 * H * D * float(sum(a * b for a, b in zip(q_lens, k_lens)))
+    tf = flops / (ms * 1e-3) / 1e12
+    clock_mhz, _ = da.dit_attn_last_launch_clock(ctx)
+    return {"metric": "DiT cross-attention TFLOP/s (bf16), 1 GPU", "value": round(tf, 2), "unit": "TFLOP/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "dtype": "bf16",
+            "data": "synthetic", "config": {"workload": "6x4352 + 20506 latent queries against 512 text keys each, 24 heads, head_dim 128"},
+            "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "shader_clock_mhz": round(clock_mhz, 1),
+                         "algorithmic_hbm_bytes": int(2 * (sum(q_lens) * 2 + sum(k_lens) * 2) * H * D)}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,6 +163,9 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other configurations (reported under per_config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--op", default="attn", choices=["attn", "merge", "cross"],
+                    help="attn: the denoising-step self-attention (the headline line); merge / cross: one line for the "
+                         "partial-result merge kernel (HBM bound) or for cross-attention against text keys")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device-to-device copy (a kernel of known HBM traffic, for counter scaling)")
     args = ap.parse_args()
@@ -133,6 +191,10 @@ def main():
                           "launches": 3}), flush=True)
         return
     ctx = da.dit_attn_create(0)
+    if args.op != "attn":
+        print(json.dumps(bench_other(da, torch, ctx, args)), flush=True)
+        da.dit_attn_destroy(ctx)
+        return
 
     w = make_workload(args.workload, args.seed)
     flops = attention_flops(w.cu_seqlens, w.n_heads, w.head_dim)

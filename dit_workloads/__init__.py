@@ -25,6 +25,8 @@ import numpy as np
 
 __all__ = [
     "Workload",
+    "CrossWorkload",
+    "make_cross",
     "CONFIG_NAMES",
     "f32_to_bf16_bits",
     "bf16_bits_to_f32",
@@ -130,6 +132,38 @@ def make_custom(seq_lens, n_heads: int, head_dim: int, seed: int, *, scale: floa
     return Workload(name=name, q=q, k=k, v=v, cu_seqlens=cu, n_heads=n_heads, head_dim=head_dim,
                     scale=float(scale), seed=seed,
                     meta={"head_scale": None if hs is None else hs.tolist()})
+
+
+@dataclass
+class CrossWorkload:
+    """Cross-attention pack: q [Tq, H, D]; k, v [Tk, H, D] (uint16 bf16 bits); separate boundaries."""
+    q: np.ndarray
+    k: np.ndarray
+    v: np.ndarray
+    cu_seqlens_q: np.ndarray
+    cu_seqlens_k: np.ndarray
+    n_heads: int
+    head_dim: int
+    scale: float
+    seed: int
+
+
+def make_cross(q_lens, k_lens, n_heads: int, head_dim: int, seed: int, *, scale: float | None = None) -> CrossWorkload:
+    """Queries of the given lengths against keys of the given lengths (same number of sequences, zeros allowed), N(0,1)
+    values rounded to bf16.  The DiT models of the paper's evaluation condition on text (Section 2.1): latent queries
+    (thousands of tokens) against a few hundred text keys is the typical shape."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    ql, kl = np.asarray(list(q_lens), dtype=np.int64), np.asarray(list(k_lens), dtype=np.int64)
+    assert len(ql) == len(kl)
+    cq, ck = np.zeros(len(ql) + 1, dtype=np.int32), np.zeros(len(kl) + 1, dtype=np.int32)
+    cq[1:], ck[1:] = np.cumsum(ql), np.cumsum(kl)
+    q = _draw_bf16(rng, (int(cq[-1]), n_heads, head_dim), None)
+    k = _draw_bf16(rng, (int(ck[-1]), n_heads, head_dim), None)
+    v = _draw_bf16(rng, (int(ck[-1]), n_heads, head_dim), None)
+    if scale is None:
+        scale = 1.0 / math.sqrt(head_dim)
+    return CrossWorkload(q=q, k=k, v=v, cu_seqlens_q=cq, cu_seqlens_k=ck, n_heads=n_heads, head_dim=head_dim,
+                         scale=float(scale), seed=seed)
 
 
 def make_workload(name: str, seed: int | None = None) -> Workload:

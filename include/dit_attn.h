@@ -44,6 +44,7 @@ extern "C" {
 #define DIT_ATTN_ERR_ALIGN         (-7)  /* q, k, v or out is not 16-byte aligned */
 #define DIT_ATTN_ERR_CAPACITY      (-8)  /* output buffer of dit_attn_plan too small */
 #define DIT_ATTN_ERR_KERNEL        (-9)  /* dit_attn_set_kernel: no such kernel */
+#define DIT_ATTN_ERR_PARTS         (-10) /* dit_attn_merge: n_parts outside 1..8 */
 
 typedef struct dit_attn_ctx dit_attn_ctx; /* opaque */
 
@@ -96,6 +97,49 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx,
  * have synchronised every stream the context was used on.  NULL is a no-op.
  */
 void dit_attn_destroy(dit_attn_ctx* ctx);
+
+/*
+ * The same operation, also returning the row-wise log-sum-exp
+ *     lse[r, h] = ln sum_j exp(scale * <Q[r,h,:], K[j,h,:]>)     (natural log, fp32, [T, H] contiguous, DEVICE)
+ * which is what makes results over disjoint key sets combinable (dit_attn_merge).  Sequence parallelism along the
+ * sequence - the ring half of the unified sequence parallelism that the paper's elastic SP builds on (Section 5,
+ * Section 4.3) - hands a GPU one block of keys per step and needs exactly this pair per block.
+ * lse must be 4-byte aligned and hold total_tokens * n_heads floats; everything else as dit_attn_varlen_fwd.
+ */
+int dit_attn_varlen_fwd_lse(dit_attn_ctx* ctx,
+                            const void* q, const void* k, const void* v,
+                            const int32_t* cu_seqlens, int32_t n_seqs,
+                            int32_t n_heads, int32_t head_dim, float scale,
+                            void* out, float* lse, void* stream);
+
+/*
+ * Cross-attention over a packed batch (paper Section 2.1: the DiT blocks also attend to the text tokens for text
+ * alignment): queries and keys have separate boundaries.  Sequence i's query rows
+ * cu_seqlens_q[i] .. cu_seqlens_q[i+1] of q ([Tq, H, D]) see key rows cu_seqlens_k[i] .. cu_seqlens_k[i+1] of k and v
+ * ([Tk, H, D]); both arrays are HOST pointers with n_seqs + 1 entries starting at 0, non-decreasing.  out is
+ * [Tq, H, D]; lse ([Tq, H], DEVICE) may be NULL.  Query rows of a sequence that has no keys get O = 0 and
+ * lse = -inf (an empty sum).  Errors and all other arguments as dit_attn_varlen_fwd.
+ */
+int dit_attn_cross_varlen_fwd(dit_attn_ctx* ctx,
+                              const void* q, const void* k, const void* v,
+                              const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int32_t n_seqs,
+                              int32_t n_heads, int32_t head_dim, float scale,
+                              void* out, float* lse, void* stream);
+
+/*
+ * Merge n_parts (1..8) partial results of the SAME queries over DISJOINT key sets (paper Section 5: sequence
+ * parallelism splits a long video's sequence over GPUs; each block of keys yields one partial result):
+ *     lse = ln sum_p exp(lse_p),     O = sum_p exp(lse_p - lse) O_p.
+ * o_parts / lse_parts: HOST arrays of n_parts DEVICE pointers, each to bf16 [total_rows, H, D] / fp32
+ * [total_rows, H] as written by dit_attn_varlen_fwd_lse or dit_attn_cross_varlen_fwd.  A part whose lse is -inf in a
+ * row has weight 0 there; a row whose parts are all -inf becomes 0 with lse -inf.  out may alias one of the parts;
+ * lse_out may be NULL.  fp32 arithmetic, bf16 output rounded to nearest even.  Enqueues one kernel on `stream`.
+ * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL, _HEAD_DIM, _N_HEADS, _PARTS, _CU_SEQLENS (total_rows < 0), _ALIGN, _HIP.
+ */
+int dit_attn_merge(dit_attn_ctx* ctx,
+                   const void* const* o_parts, const float* const* lse_parts, int32_t n_parts,
+                   int64_t total_rows, int32_t n_heads, int32_t head_dim,
+                   void* out, float* lse_out, void* stream);
 
 /*
  * Kernel choice of a context.  The library has three kernels for the same

@@ -23,6 +23,9 @@ __all__ = [
     "dit_attn_version",
     "dit_attn_create",
     "dit_attn_varlen_fwd",
+    "dit_attn_varlen_fwd_lse",
+    "dit_attn_cross_varlen_fwd",
+    "dit_attn_merge",
     "dit_attn_destroy",
     "dit_attn_last_error",
     "dit_attn_plan",
@@ -49,6 +52,7 @@ ERROR_NAMES = {
     -7: "DIT_ATTN_ERR_ALIGN",
     -8: "DIT_ATTN_ERR_CAPACITY",
     -9: "DIT_ATTN_ERR_KERNEL",
+    -10: "DIT_ATTN_ERR_PARTS",
 }
 
 
@@ -81,6 +85,12 @@ def load_library() -> ctypes.CDLL:
     lib.dit_attn_varlen_fwd.argtypes = [vp, vp, vp, vp, i32p, i32, i32, i32, ctypes.c_float, vp, vp]
     lib.dit_attn_destroy.restype = None
     lib.dit_attn_destroy.argtypes = [vp]
+    lib.dit_attn_varlen_fwd_lse.restype = ctypes.c_int
+    lib.dit_attn_varlen_fwd_lse.argtypes = [vp, vp, vp, vp, i32p, i32, i32, i32, ctypes.c_float, vp, vp, vp]
+    lib.dit_attn_cross_varlen_fwd.restype = ctypes.c_int
+    lib.dit_attn_cross_varlen_fwd.argtypes = [vp, vp, vp, vp, i32p, i32p, i32, i32, i32, ctypes.c_float, vp, vp, vp]
+    lib.dit_attn_merge.restype = ctypes.c_int
+    lib.dit_attn_merge.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i64, i32, i32, vp, vp, vp]
     lib.dit_attn_last_error.restype = ctypes.c_char_p
     lib.dit_attn_last_error.argtypes = [vp]
     lib.dit_attn_set_kernel.restype = ctypes.c_int
@@ -167,6 +177,55 @@ def dit_attn_varlen_fwd(ctx, q, k, v, cu_seqlens, n_heads: int, head_dim: int, s
                                  ctypes.c_void_p(_ptr(v)), cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
                                  int(n_seqs), int(n_heads), int(head_dim), float(scale),
                                  ctypes.c_void_p(_ptr(out)), ctypes.c_void_p(_ptr(stream)))
+    if rc != 0:
+        raise DitAttnError(rc, dit_attn_last_error(ctx))
+
+
+def dit_attn_varlen_fwd_lse(ctx, q, k, v, cu_seqlens, n_heads: int, head_dim: int, scale: float, out, lse, stream=None,
+                            n_seqs: int | None = None) -> None:
+    """dit_attn_varlen_fwd that also writes lse (device fp32 [T, n_heads], natural log); see include/dit_attn.h."""
+    lib = load_library()
+    cu = _cu_array(cu_seqlens)
+    if n_seqs is None:
+        n_seqs = len(cu) - 1
+    rc = lib.dit_attn_varlen_fwd_lse(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(q)), ctypes.c_void_p(_ptr(k)),
+                                     ctypes.c_void_p(_ptr(v)), cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                     int(n_seqs), int(n_heads), int(head_dim), float(scale),
+                                     ctypes.c_void_p(_ptr(out)), ctypes.c_void_p(_ptr(lse)), ctypes.c_void_p(_ptr(stream)))
+    if rc != 0:
+        raise DitAttnError(rc, dit_attn_last_error(ctx))
+
+
+def dit_attn_cross_varlen_fwd(ctx, q, k, v, cu_seqlens_q, cu_seqlens_k, n_heads: int, head_dim: int, scale: float, out,
+                              lse=None, stream=None, n_seqs: int | None = None) -> None:
+    """Cross-attention with separate query and key boundaries; lse may be None.  See include/dit_attn.h."""
+    lib = load_library()
+    cq = _cu_array(cu_seqlens_q)
+    ck = None if cu_seqlens_k is None else _cu_array(cu_seqlens_k)
+    if n_seqs is None:
+        n_seqs = len(cq) - 1
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    rc = lib.dit_attn_cross_varlen_fwd(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(q)), ctypes.c_void_p(_ptr(k)),
+                                       ctypes.c_void_p(_ptr(v)), cq.ctypes.data_as(i32p),
+                                       None if ck is None else ck.ctypes.data_as(i32p),
+                                       int(n_seqs), int(n_heads), int(head_dim), float(scale),
+                                       ctypes.c_void_p(_ptr(out)), ctypes.c_void_p(_ptr(lse)), ctypes.c_void_p(_ptr(stream)))
+    if rc != 0:
+        raise DitAttnError(rc, dit_attn_last_error(ctx))
+
+
+def dit_attn_merge(ctx, o_parts, lse_parts, total_rows: int, n_heads: int, head_dim: int, out, lse_out=None,
+                   stream=None) -> None:
+    """Merge partial results over disjoint key sets; o_parts / lse_parts: sequences of device buffers.  See the header."""
+    lib = load_library()
+    n = len(o_parts)
+    vp = ctypes.c_void_p
+    o_arr = (vp * max(n, 1))(*[vp(_ptr(x)) for x in o_parts])
+    l_arr = (vp * max(n, 1))(*[vp(_ptr(x)) for x in lse_parts]) if len(lse_parts) == n else None
+    if l_arr is None:
+        raise ValueError("o_parts and lse_parts must have the same length")
+    rc = lib.dit_attn_merge(vp(ctx), o_arr, l_arr, int(n), int(total_rows), int(n_heads), int(head_dim), vp(_ptr(out)),
+                            vp(_ptr(lse_out)), vp(_ptr(stream)))
     if rc != 0:
         raise DitAttnError(rc, dit_attn_last_error(ctx))
 

@@ -12,12 +12,14 @@
 #include <vector>
 
 #include "attn_fwd.h"
+#include "merge.h"
 #include "plan.h"
 
 namespace {
 
 struct CachedPlan {
-  std::vector<int32_t> cu;  // key: cu_seqlens contents
+  std::vector<int32_t> cu;  // key: cu_seqlens contents (of the queries)
+  std::vector<int32_t> cu_k;  // key: key boundaries, empty when they are the query boundaries
   int32_t n_heads = 0;
   int32_t head_dim = 0;
   dit::AttnKernel kernel = dit::AttnKernel::kIndependent128;
@@ -210,13 +212,20 @@ int64_t dit_attn_plan(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads
   return n;
 }
 
-int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
-                        int32_t n_seqs, int32_t n_heads, int32_t head_dim, float scale, void* out, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// cu_k == nullptr: self-attention (keys share the query boundaries).  lse may be nullptr.
+int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, const int32_t* cu_seqlens, const int32_t* cu_k,
+            int32_t n_seqs, int32_t n_heads, int32_t head_dim, float scale, void* out, float* lse, void* stream) {
   if (!ctx) return DIT_ATTN_ERR_NULL;
   ctx->error.clear();
   std::string msg;
-  const int rc = check_shape_args(cu_seqlens, n_seqs, n_heads, head_dim, msg);
+  int rc = check_shape_args(cu_seqlens, n_seqs, n_heads, head_dim, msg);
   if (rc != DIT_ATTN_OK) return fail(ctx, rc, msg);
+  if (cu_k && dit::plan_validate(cu_k, n_seqs) != 0)
+    return fail(ctx, DIT_ATTN_ERR_CU_SEQLENS, "cu_seqlens_k must start at 0 and be non-decreasing");
   if (!std::isfinite(scale)) return fail(ctx, DIT_ATTN_ERR_SCALE, "scale must be finite");
   const int64_t total = n_seqs > 0 ? cu_seqlens[n_seqs] : 0;
   if (n_seqs == 0 || total == 0) return DIT_ATTN_OK;
@@ -224,6 +233,7 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
   const uintptr_t bits = reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) |
                          reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(out);
   if (bits & 15u) return fail(ctx, DIT_ATTN_ERR_ALIGN, "q, k, v and out must be 16-byte aligned");
+  if (reinterpret_cast<uintptr_t>(lse) & 3u) return fail(ctx, DIT_ATTN_ERR_ALIGN, "lse must be 4-byte aligned");
 
   DeviceGuard guard;
   hipError_t e = guard.enter(ctx->device);
@@ -237,7 +247,8 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
                                                         : dit::attn_fwd_select(cu_seqlens, n_seqs, n_heads, ctx->n_cus);
   for (auto& p : ctx->plans) {
     if (p->n_heads == n_heads && p->head_dim == head_dim && p->kernel == kernel && p->cu.size() == cu_n &&
-        std::memcmp(p->cu.data(), cu_seqlens, cu_n * sizeof(int32_t)) == 0) {
+        p->cu_k.size() == (cu_k ? cu_n : 0) && std::memcmp(p->cu.data(), cu_seqlens, cu_n * sizeof(int32_t)) == 0 &&
+        (!cu_k || std::memcmp(p->cu_k.data(), cu_k, cu_n * sizeof(int32_t)) == 0)) {
       plan = p.get();
       break;
     }
@@ -247,10 +258,11 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
     try {
       np.reset(new CachedPlan());
       np->cu.assign(cu_seqlens, cu_seqlens + cu_n);
+      if (cu_k) np->cu_k.assign(cu_k, cu_k + cu_n);
       np->n_heads = n_heads;
       np->head_dim = head_dim;
       np->kernel = kernel;
-      dit::plan_build(cu_seqlens, n_seqs, n_heads, dit::attn_fwd_block_m(np->kernel), np->host_items);
+      dit::plan_build_cross(cu_seqlens, cu_k ? cu_k : cu_seqlens, n_seqs, n_heads, dit::attn_fwd_block_m(np->kernel), np->host_items);
     } catch (...) {
       return fail(ctx, DIT_ATTN_ERR_HIP, "out of host memory while building the work-list");
     }
@@ -276,6 +288,15 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
   }
   plan->last_use = ++ctx->tick;
 
+  // Query rows of a sequence without keys: O = 0, lse = -inf (an empty sum).
+  if (cu_k) {
+    for (int32_t i = 0; i < n_seqs; ++i) {
+      if (cu_k[i + 1] == cu_k[i] && cu_seqlens[i + 1] > cu_seqlens[i]) {
+        e = dit::fill_rows_launch(out, lse, cu_seqlens[i], cu_seqlens[i + 1] - cu_seqlens[i], n_heads, head_dim, s);
+        if (e != hipSuccess) return fail_hip(ctx, e, "fill kernel launch");
+      }
+    }
+  }
   const uint32_t n_items = static_cast<uint32_t>(plan->host_items.size());
   if (n_items == 0) return DIT_ATTN_OK;
   const int64_t max_grid = static_cast<int64_t>(ctx->n_cus) * dit::attn_fwd_wgs_per_cu(plan->kernel);
@@ -286,6 +307,7 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
   p.k = k;
   p.v = v;
   p.out = out;
+  p.lse = lse;
   p.items = plan->dev_items;
   p.sync = ctx->sync;
   p.n_items = n_items;
@@ -294,6 +316,62 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const v
   p.negate = scale < 0.f ? 1 : 0;
   e = dit::attn_fwd_launch(p, plan->kernel, head_dim, grid, s);
   if (e != hipSuccess) return fail_hip(ctx, e, "kernel launch");
+  return DIT_ATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dit_attn_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                        int32_t n_seqs, int32_t n_heads, int32_t head_dim, float scale, void* out, void* stream) {
+  return forward(ctx, q, k, v, cu_seqlens, nullptr, n_seqs, n_heads, head_dim, scale, out, nullptr, stream);
+}
+
+int dit_attn_varlen_fwd_lse(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                            int32_t n_seqs, int32_t n_heads, int32_t head_dim, float scale, void* out, float* lse,
+                            void* stream) {
+  if (ctx && !lse && n_seqs > 0 && cu_seqlens && cu_seqlens[n_seqs] > 0) return fail(ctx, DIT_ATTN_ERR_NULL, "lse must be non-NULL");
+  return forward(ctx, q, k, v, cu_seqlens, nullptr, n_seqs, n_heads, head_dim, scale, out, lse, stream);
+}
+
+int dit_attn_cross_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, const int32_t* cu_seqlens_q,
+                              const int32_t* cu_seqlens_k, int32_t n_seqs, int32_t n_heads, int32_t head_dim, float scale,
+                              void* out, float* lse, void* stream) {
+  if (ctx && !cu_seqlens_k) return fail(ctx, DIT_ATTN_ERR_NULL, "cu_seqlens_k is NULL");
+  return forward(ctx, q, k, v, cu_seqlens_q, cu_seqlens_k, n_seqs, n_heads, head_dim, scale, out, lse, stream);
+}
+
+int dit_attn_merge(dit_attn_ctx* ctx, const void* const* o_parts, const float* const* lse_parts, int32_t n_parts,
+                   int64_t total_rows, int32_t n_heads, int32_t head_dim, void* out, float* lse_out, void* stream) {
+  if (!ctx) return DIT_ATTN_ERR_NULL;
+  ctx->error.clear();
+  if (head_dim != 64 && head_dim != 128) return fail(ctx, DIT_ATTN_ERR_HEAD_DIM, "head_dim must be 64 or 128");
+  if (n_heads < 1 || n_heads > 65535) return fail(ctx, DIT_ATTN_ERR_N_HEADS, "n_heads must be in 1..65535");
+  if (n_parts < 1 || n_parts > dit::kMaxMergeParts)
+    return fail(ctx, DIT_ATTN_ERR_PARTS, "n_parts must be in 1.." + std::to_string(dit::kMaxMergeParts));
+  if (total_rows < 0) return fail(ctx, DIT_ATTN_ERR_CU_SEQLENS, "total_rows must be >= 0");
+  if (total_rows == 0) return DIT_ATTN_OK;
+  if (!o_parts || !lse_parts || !out) return fail(ctx, DIT_ATTN_ERR_NULL, "o_parts, lse_parts and out must be non-NULL");
+  dit::MergeParams p{};
+  uintptr_t bits = reinterpret_cast<uintptr_t>(out), bits4 = reinterpret_cast<uintptr_t>(lse_out);
+  for (int32_t i = 0; i < n_parts; ++i) {
+    if (!o_parts[i] || !lse_parts[i]) return fail(ctx, DIT_ATTN_ERR_NULL, "a part pointer is NULL");
+    p.o[i] = o_parts[i];
+    p.lse[i] = lse_parts[i];
+    bits |= reinterpret_cast<uintptr_t>(o_parts[i]);
+    bits4 |= reinterpret_cast<uintptr_t>(lse_parts[i]);
+  }
+  if ((bits & 15u) || (bits4 & 3u)) return fail(ctx, DIT_ATTN_ERR_ALIGN, "o parts and out must be 16-byte, lse arrays 4-byte aligned");
+  p.out = out;
+  p.lse_out = lse_out;
+  p.chunks_per_row = head_dim * 2 / 16;
+  p.n_chunks = total_rows * n_heads * p.chunks_per_row;
+  DeviceGuard guard;
+  hipError_t e = guard.enter(ctx->device);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+  e = dit::merge_launch(p, n_parts, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip(ctx, e, "merge kernel launch");
   return DIT_ATTN_OK;
 }
 

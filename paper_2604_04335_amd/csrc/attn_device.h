@@ -438,11 +438,12 @@ __device__ __forceinline__ void load_q(const AttnParams& p, const Lane<T>& L, co
   }
 }
 
-// Epilogue: O^T / l -> bf16 -> out.  Lane holds d = 32*db + 8*g + 4*hh + j (i = 4*g + j) of query l32.
+// Epilogue: O^T / l -> bf16 -> out, and, if asked for, lse = ln sum_j exp(scale * s_j) = ln 2 * (c * m + log2 l).
+// Lane holds d = 32*db + 8*g + 4*hh + j (i = 4*g + j) of query l32.
 template <class T>
 __device__ __forceinline__ void store_out(const AttnParams& p, const Lane<T>& L, const ItemU& it, int64_t row_stride_b,
                                           int64_t head_off, int qrow, bool row_valid, const f32x16 (&o)[T::NDB],
-                                          float l_run) {
+                                          float l_run, float m_ref) {
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   if (row_valid) {
     const float inv = 1.0f / l_tot;
@@ -456,6 +457,8 @@ __device__ __forceinline__ void store_out(const AttnParams& p, const Lane<T>& L,
         w[1] = pack_bf16x2(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
         *reinterpret_cast<u32x2*>(optr + (32 * db + 8 * g) * 2) = w;
       }
+    if (p.lse != nullptr && L.hh == 0)
+      p.lse[(int64_t)(it.q_start + qrow) * p.n_heads + it.head] = 0.69314718055994530942f * (m_ref * p.c_log2 + __builtin_amdgcn_logf(l_tot));
   }
 }
 

@@ -8,10 +8,11 @@
 namespace dit {
 
 struct AttnParams {
-  const void* q;            // bf16 [T, H, D]
-  const void* k;
+  const void* q;            // bf16 [Tq, H, D]
+  const void* k;            // bf16 [Tk, H, D] (Tk = Tq and the same boundaries for self-attention)
   const void* v;
   void* out;                // bf16 [T, H, D]
+  float* lse;               // fp32 [T, H] or nullptr: natural-log sum of exp(scale * score) of every (query row, head)
   const WorkItem* items;    // device work-list
   uint32_t* sync;           // device, 8 words (8-byte aligned): [0] items taken so far, [1] workgroups finished,
                             // [2..3] shader cycles and [4..5] 100 MHz ticks workgroup 0 of the last launch ran for.
@@ -47,3 +48,4 @@ hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim,
 hipError_t attn_fwd_wide_launch(const AttnParams& p, int head_dim, int grid, hipStream_t stream);
 
 }  // namespace dit
+

@@ -77,7 +77,7 @@ attn_fwd_kernel(AttnParams p) {
       for (int db = 0; db < T::NDB; ++db) va[db] ^= T::TILE_B;
     }
 
-    store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run);
+    store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run, m_ref);
     wg_barrier();  // the next item's first loads overwrite the buffers of parity 0
   }
   launch_clock_end(p, clock0);
@@ -201,7 +201,7 @@ attn_fwd_pp_kernel(AttnParams p) {
     __builtin_amdgcn_s_setprio(0);
     wg_barrier();
 
-    store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run);
+    store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run, m_ref);
     if (group == 0) wg_barrier();  // group 0 idles (after its stores) while group 1 runs its last matrix phase
   }
   launch_clock_end(p, clock0);

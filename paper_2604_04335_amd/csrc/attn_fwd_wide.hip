@@ -455,7 +455,7 @@ attn_fwd_wide_kernel(AttnParams p) {
 
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      store_out<T>(p, L, it, row_stride_b, head_off, qrow[h], row_valid[h], o[h], l_run[h]);
+      store_out<T>(p, L, it, row_stride_b, head_off, qrow[h], row_valid[h], o[h], l_run[h], m_ref[h]);
       SCHED_FENCE();
     }
   }

@@ -29,4 +29,11 @@ int plan_validate(const int32_t* cu_seqlens, int32_t n_seqs);
 void plan_build(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int32_t block_m,
                 std::vector<WorkItem>& items);
 
+// The same with separate query and key boundaries (cross-attention, paper Section 2.1: DiT blocks attend to the text
+// tokens): sequence i's query rows cu_q[i]..cu_q[i+1] of q see key rows cu_k[i]..cu_k[i+1] of k and v.  Sequences with
+// no query rows or no key rows contribute no items (the caller zeroes the output rows of the latter).  Sequences with
+// the most keys come first.
+void plan_build_cross(const int32_t* cu_q, const int32_t* cu_k, int32_t n_seqs, int32_t n_heads, int32_t block_m,
+                      std::vector<WorkItem>& items);
+
 }  // namespace dit

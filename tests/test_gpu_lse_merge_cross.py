@@ -1,0 +1,212 @@
+"""GPU parity of the log-sum-exp output, the merge of partial results and cross-attention against the CPU oracle.
+
+Tolerances.  O: the attention bars of tests/gpu_util.py (max-abs 2e-2 and relative L2 1e-2).  lse: computed in fp32 as
+ln 2 * (c*m + log2 l) with l summed in fp32 from unrounded probabilities; its error is a few fp32 ulps of |c*m| (up to
+~60 here) plus the hardware log2's ~1 ulp and the fp32 summation error of l (relative ~1e-6): 1e-4 absolute is asserted.
+Merged O: the parts are bf16 (2^-9 relative each) and the result is rounded once more, so the same attention bars apply.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_04335_amd as da
+from dit_workloads import bf16_bits_to_f32, make_cross, make_custom, make_workload, sample_rows
+from oracle import dit_attn_oracle as orc
+
+sys.path.insert(0, os.path.dirname(__file__))
+from gpu_util import MAX_ABS_TOL, REL_L2_TOL, assert_parity, to_bits, to_dev, widen  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+LSE_TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    da.load_library()
+    c = da.dit_attn_create(0)
+    yield c
+    da.dit_attn_destroy(c)
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _fwd_lse(ctx, w, kernel=None):
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    out = torch.empty_like(q)
+    lse = torch.full((q.shape[0], w.n_heads), float("nan"), dtype=torch.float32, device="cuda")
+    if kernel is not None:
+        da.dit_attn_set_kernel(ctx, kernel)
+    try:
+        da.dit_attn_varlen_fwd_lse(ctx, q, k, v, w.cu_seqlens, w.n_heads, w.head_dim, w.scale, out, lse, _stream())
+    finally:
+        da.dit_attn_set_kernel(ctx, da.KERNEL_AUTO)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+@pytest.mark.parametrize("head_dim,kernel", [(64, None), (128, None), (128, da.KERNEL_PINGPONG), (128, da.KERNEL_WIDE), (64, da.KERNEL_WIDE)])
+def test_lse_matches_oracle(ctx, head_dim, kernel):
+    w = make_custom([300, 1, 129, 64, 777], 3, head_dim, seed=41)
+    out, lse = _fwd_lse(ctx, w, kernel)
+    ref_o, ref_l = orc.attention_varlen_lse(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    assert_parity(to_bits(out), ref_o, "O with lse requested")
+    got = lse.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got - ref_l)) <= LSE_TOL, np.max(np.abs(got - ref_l))
+    # O does not depend on whether lse is asked for
+    out2 = torch.empty_like(out)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    if kernel is not None:
+        da.dit_attn_set_kernel(ctx, kernel)
+    da.dit_attn_varlen_fwd(ctx, q, k, v, w.cu_seqlens, w.n_heads, w.head_dim, w.scale, out2, _stream())
+    da.dit_attn_set_kernel(ctx, da.KERNEL_AUTO)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+
+
+def test_lse_negative_and_zero_scale_and_large_logits(ctx):
+    w = make_custom([150, 70], 2, 64, seed=42)
+    for scale in (-0.4, 0.0, 3.0):
+        w.scale = scale
+        _, lse = _fwd_lse(ctx, w)
+        _, ref = orc.attention_varlen_lse(w.q, w.k, w.v, w.cu_seqlens, scale)
+        tol = LSE_TOL * max(1.0, float(np.max(np.abs(ref))) / 60.0)
+        assert np.max(np.abs(lse.cpu().numpy() - ref)) <= tol
+
+
+def test_lse_full_size_sampled_rows(ctx):
+    """mixed_varlen at full size, in the bench's launch configuration: one head of a stratified row sample."""
+    w = make_workload("mixed_varlen")
+    _, lse = _fwd_lse(ctx, w)
+    got = lse.cpu().numpy()
+    cu, h = w.cu_seqlens, 3
+    for r in sample_rows(cu, seed=5, block=2048):
+        i = int(np.searchsorted(cu, r, side="right") - 1)
+        ref = orc.logsumexp_scores(orc.widen_bf16(w.q[r:r + 1, h]), orc.widen_bf16(w.k[cu[i]:cu[i + 1], h]), w.scale)
+        assert abs(got[r, h] - ref[0]) <= LSE_TOL
+
+
+@pytest.mark.parametrize("bounds", [(0, 700, 1300), (0, 64, 65, 1000, 1300), (0, 1300)])
+def test_split_keys_then_merge_equals_full_attention(ctx, bounds):
+    """What a ring step does: the same queries against blocks of keys, one call each, then one merge."""
+    L, H, D = 1300, 3, 128
+    w = make_custom([L], H, D, seed=43)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    outs, lses = [], []
+    for a, b in zip(bounds[:-1], bounds[1:]):
+        o = torch.empty_like(q)
+        l = torch.empty((L, H), dtype=torch.float32, device="cuda")
+        da.dit_attn_cross_varlen_fwd(ctx, q, k[a:b].contiguous(), v[a:b].contiguous(), [0, L], [0, b - a], H, D, w.scale, o, l, _stream())
+        outs.append(o); lses.append(l)
+    merged = torch.empty_like(q)
+    lse = torch.empty((L, H), dtype=torch.float32, device="cuda")
+    da.dit_attn_merge(ctx, outs, lses, L, H, D, merged, lse, _stream())
+    torch.cuda.synchronize()
+    ref_o, ref_l = orc.attention_varlen_lse(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    assert_parity(to_bits(merged), ref_o, f"merge of {len(outs)} key blocks")
+    assert np.max(np.abs(lse.cpu().numpy() - ref_l)) <= LSE_TOL
+    # merging into one of the parts gives the same bits
+    da.dit_attn_merge(ctx, outs, lses, L, H, D, outs[0], None, _stream())
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0].view(torch.int16), merged.view(torch.int16))
+
+
+@pytest.mark.parametrize("n_parts,head_dim", [(1, 64), (2, 128), (5, 64), (8, 128)])
+def test_merge_kernel_against_oracle_on_random_parts(ctx, n_parts, head_dim):
+    T, H = 517, 3
+    g = np.random.Generator(np.random.PCG64(44 + n_parts))
+    from dit_workloads import f32_to_bf16_bits
+    o_bits = [f32_to_bf16_bits(g.standard_normal((T, H, head_dim)).astype(np.float32)) for _ in range(n_parts)]
+    lse = [(4.0 * g.standard_normal((T, H))).astype(np.float32) for _ in range(n_parts)]
+    if n_parts >= 2:
+        lse[1][5] = -np.inf                      # a part without keys in one row
+        o_bits[1][5] = 0x7FC0                    # ... whose O is NaN: must not leak
+        for p in range(n_parts):
+            lse[p][9, 1] = -np.inf               # a (row, head) with no keys at all
+    outs = [to_dev(x) for x in o_bits]
+    lses = [torch.from_numpy(x).cuda() for x in lse]
+    out = torch.empty_like(outs[0])
+    lo = torch.empty((T, H), dtype=torch.float32, device="cuda")
+    da.dit_attn_merge(ctx, outs, lses, T, H, head_dim, out, lo, _stream())
+    torch.cuda.synchronize()
+    o64 = np.stack([np.where(np.isfinite(widen(b)), widen(b), 0.0) for b in o_bits])
+    ref_o, ref_l = orc.merge_partials(o64, np.stack(lse).astype(np.float64))
+    got = widen(to_bits(out))
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got - ref_o)) <= MAX_ABS_TOL and np.sqrt(np.sum((got - ref_o) ** 2) / np.sum(ref_o ** 2)) <= REL_L2_TOL
+    gl = lo.cpu().numpy().astype(np.float64)
+    fin = np.isfinite(ref_l)
+    assert np.array_equal(np.isfinite(gl), fin) and np.all(gl[~fin] == -np.inf)
+    assert np.max(np.abs(gl[fin] - ref_l[fin])) <= LSE_TOL
+    if n_parts >= 2:
+        assert np.all(got[9, 1] == 0.0)
+
+
+@pytest.mark.parametrize("q_lens,k_lens,H,D", [
+    ([300, 5, 129], [77, 226, 1], 3, 128),          # ragged, keys shorter than one tile
+    ([1000, 0, 64, 200], [226, 50, 0, 512], 2, 64),  # a sequence without queries, one without keys
+    ([4352, 4352], [226, 512], 4, 128),              # latent queries against text keys at the image-step length
+])
+def test_cross_attention_matches_oracle(ctx, q_lens, k_lens, H, D):
+    w = make_cross(q_lens, k_lens, H, D, seed=45)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    SENT = 0x7FC1
+    out = torch.full(q.shape, SENT, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    lse = torch.full((q.shape[0], H), float("nan"), dtype=torch.float32, device="cuda")
+    da.dit_attn_cross_varlen_fwd(ctx, q, k, v, w.cu_seqlens_q, w.cu_seqlens_k, H, D, w.scale, out, lse, _stream())
+    torch.cuda.synchronize()
+    ref_o, ref_l = orc.attention_cross_varlen(w.q, w.k, w.v, w.cu_seqlens_q, w.cu_seqlens_k, w.scale)
+    assert_parity(to_bits(out), ref_o, "cross-attention")
+    gl = lse.cpu().numpy().astype(np.float64)
+    fin = np.isfinite(ref_l)
+    assert np.array_equal(np.isfinite(gl), fin) and np.all(gl[~fin] == -np.inf)
+    assert np.max(np.abs(gl[fin] - ref_l[fin])) <= LSE_TOL
+    # rows of a sequence without keys are exactly zero
+    got = to_bits(out)
+    for i in range(len(q_lens)):
+        if k_lens[i] == 0:
+            assert np.all(got[w.cu_seqlens_q[i]:w.cu_seqlens_q[i + 1]] == 0)
+    # lse is optional, and the same boundaries for q and k reproduce self-attention bit for bit
+    out2 = torch.empty_like(out)
+    da.dit_attn_cross_varlen_fwd(ctx, q, k, v, w.cu_seqlens_q, w.cu_seqlens_k, H, D, w.scale, out2, None, _stream())
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+
+
+def test_cross_with_equal_boundaries_is_self_attention(ctx):
+    w = make_custom([500, 33], 2, 128, seed=46)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    a, b = torch.empty_like(q), torch.empty_like(q)
+    da.dit_attn_varlen_fwd(ctx, q, k, v, w.cu_seqlens, 2, 128, w.scale, a, _stream())
+    da.dit_attn_cross_varlen_fwd(ctx, q, k, v, w.cu_seqlens, w.cu_seqlens, 2, 128, w.scale, b, None, _stream())
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_new_entry_points_reject_bad_arguments(ctx):
+    w = make_custom([100], 2, 64, seed=47)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    out = torch.empty_like(q)
+    lse = torch.empty((100, 2), dtype=torch.float32, device="cuda")
+    with pytest.raises(da.DitAttnError) as e:
+        da.dit_attn_varlen_fwd_lse(ctx, q, k, v, w.cu_seqlens, 2, 64, w.scale, out, None, _stream())
+    assert e.value.code == -1
+    with pytest.raises(da.DitAttnError) as e:
+        da.dit_attn_cross_varlen_fwd(ctx, q, k, v, w.cu_seqlens, None, 2, 64, w.scale, out, None, _stream())
+    assert e.value.code == -1
+    with pytest.raises(da.DitAttnError) as e:
+        da.dit_attn_cross_varlen_fwd(ctx, q, k, v, w.cu_seqlens, [5, 100], 2, 64, w.scale, out, None, _stream())
+    assert e.value.code == -3
+    with pytest.raises(da.DitAttnError) as e:
+        da.dit_attn_merge(ctx, [out] * 9, [lse] * 9, 100, 2, 64, out, None, _stream())
+    assert e.value.code == -10
+    with pytest.raises(da.DitAttnError) as e:
+        da.dit_attn_merge(ctx, [out], [lse], 100, 2, 96, out, None, _stream())
+    assert e.value.code == -2
+    da.dit_attn_merge(ctx, [out], [lse], 0, 2, 64, out, None, _stream())  # nothing to do
+    torch.cuda.synchronize()
