@@ -136,6 +136,27 @@ def bench_other(da, torch, ctx, args):
                 "dtype": "bf16", "data": "synthetic", "config": {"workload": "merge of 4 parts, 49178 rows x 24 heads x 128"},
                 "roofline": {"bound": "hbm", "kernel": "merge_kernel<4>", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_hbm_bytes": nbytes}}
+    if args.op == "layout":
+        # one rank's shard of the sequence behind sp_shard (76112 tokens, 40 heads, 4-way head split): pack, then unpack
+        n, Hh, p = 19028, 40, 4
+        g = torch.Generator(device="cuda").manual_seed(8)
+        x = torch.randn((n, Hh, D), device="cuda", generator=g).to(torch.bfloat16)
+        y = torch.empty((p, n, Hh // p, D), dtype=torch.bfloat16, device="cuda")
+        z = torch.empty_like(x)
+
+        def both():
+            da.dit_attn_sp_pack_heads(ctx, x, y, n, Hh, D, p, stream)
+            da.dit_attn_sp_unpack_heads(ctx, y, z, n, Hh, D, p, stream)
+        ms = _time_calls(torch, both, args.steps, args.warmup)
+        nbytes = 2 * 2 * n * Hh * D * 2
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        return {"metric": "head-split layout pack + unpack, GB/s of algorithmic HBM traffic, 1 GPU", "value": round(gbs, 1),
+                "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+                "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+                "config": {"workload": "pack then unpack of [19028, 40, 128], sp degree 4"},
+                "roofline": {"bound": "hbm", "kernel": "sp_layout_kernel<true> + sp_layout_kernel<false>", "achieved": round(gbs, 1),
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                             "algorithmic_hbm_bytes": nbytes}}
     from dit_workloads import make_cross
     q_lens, k_lens = [4352] * 6 + [20506], [512] * 7   # latent queries of six images and one video against 512 text keys
     w = make_cross(q_lens, k_lens, H, D, seed=2001)
@@ -163,7 +184,7 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other configurations (reported under per_config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--op", default="attn", choices=["attn", "merge", "cross"],
+    ap.add_argument("--op", default="attn", choices=["attn", "merge", "cross", "layout"],
                     help="attn: the denoising-step self-attention (the headline line); merge / cross: one line for the "
                          "partial-result merge kernel (HBM bound) or for cross-attention against text keys")
     ap.add_argument("--copy-calibration", action="store_true",

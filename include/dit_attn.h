@@ -142,6 +142,24 @@ int dit_attn_merge(dit_attn_ctx* ctx,
                    void* out, float* lse_out, void* stream);
 
 /*
+ * Single-GPU halves of the head-split sequence-parallel exchange (paper Section 4.3: elastic sequence parallelism
+ * gives a video p in {1,2,4,8} GPUs; Section 5: the head-split half of the unified sequence parallelism).  A rank
+ * holds n_rows rows of the sequence with all n_heads heads; attention needs the whole sequence for n_heads / p heads.
+ *     pack:    src [n_rows, H, D]        -> dst [p, n_rows, H/p, D]   dst[g, r, h, :] = src[r, g*H/p + h, :]
+ *     unpack:  src [p, n_rows, H/p, D]   -> dst [n_rows, H, D]        dst[r, g*H/p + h, :] = src[g, r, h, :]
+ * Block g of pack's output is what goes to rank g before attention (the blocks a rank receives, in source-rank order,
+ * are its [L, H/p, D] input without further copying); unpack's input is the blocks a rank receives after attention,
+ * in source-rank order.  bf16, DEVICE buffers, 16-byte aligned, src and dst must not overlap.  sp_degree (p) >= 1 must
+ * divide n_heads.  Enqueues one kernel on `stream`; moves every byte once (HBM bound).
+ * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL, _HEAD_DIM, _N_HEADS (also: p does not divide n_heads), _CU_SEQLENS
+ * (n_rows < 0), _ALIGN, _HIP.
+ */
+int dit_attn_sp_pack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int64_t n_rows,
+                           int32_t n_heads, int32_t head_dim, int32_t sp_degree, void* stream);
+int dit_attn_sp_unpack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int64_t n_rows,
+                             int32_t n_heads, int32_t head_dim, int32_t sp_degree, void* stream);
+
+/*
  * Kernel choice of a context.  The library has three kernels for the same
  * operation (which one is fastest depends on the pack, Section 4.3 / Table 3:
  * image steps are short, video steps long):

@@ -26,6 +26,8 @@ __all__ = [
     "dit_attn_varlen_fwd_lse",
     "dit_attn_cross_varlen_fwd",
     "dit_attn_merge",
+    "dit_attn_sp_pack_heads",
+    "dit_attn_sp_unpack_heads",
     "dit_attn_destroy",
     "dit_attn_last_error",
     "dit_attn_plan",
@@ -89,6 +91,9 @@ def load_library() -> ctypes.CDLL:
     lib.dit_attn_varlen_fwd_lse.argtypes = [vp, vp, vp, vp, i32p, i32, i32, i32, ctypes.c_float, vp, vp, vp]
     lib.dit_attn_cross_varlen_fwd.restype = ctypes.c_int
     lib.dit_attn_cross_varlen_fwd.argtypes = [vp, vp, vp, vp, i32p, i32p, i32, i32, i32, ctypes.c_float, vp, vp, vp]
+    for fn in (lib.dit_attn_sp_pack_heads, lib.dit_attn_sp_unpack_heads):
+        fn.restype = ctypes.c_int
+        fn.argtypes = [vp, vp, vp, i64, i32, i32, i32, vp]
     lib.dit_attn_merge.restype = ctypes.c_int
     lib.dit_attn_merge.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i64, i32, i32, vp, vp, vp]
     lib.dit_attn_last_error.restype = ctypes.c_char_p
@@ -228,6 +233,24 @@ def dit_attn_merge(ctx, o_parts, lse_parts, total_rows: int, n_heads: int, head_
                             vp(_ptr(lse_out)), vp(_ptr(stream)))
     if rc != 0:
         raise DitAttnError(rc, dit_attn_last_error(ctx))
+
+
+def _sp_layout(name, ctx, src, dst, n_rows, n_heads, head_dim, sp_degree, stream):
+    vp = ctypes.c_void_p
+    rc = getattr(load_library(), name)(vp(ctx), vp(_ptr(src)), vp(_ptr(dst)), int(n_rows), int(n_heads), int(head_dim),
+                                       int(sp_degree), vp(_ptr(stream)))
+    if rc != 0:
+        raise DitAttnError(rc, dit_attn_last_error(ctx))
+
+
+def dit_attn_sp_pack_heads(ctx, src, dst, n_rows: int, n_heads: int, head_dim: int, sp_degree: int, stream=None) -> None:
+    """[n_rows, H, D] -> [p, n_rows, H/p, D] (block g goes to rank g); see include/dit_attn.h."""
+    _sp_layout("dit_attn_sp_pack_heads", ctx, src, dst, n_rows, n_heads, head_dim, sp_degree, stream)
+
+
+def dit_attn_sp_unpack_heads(ctx, src, dst, n_rows: int, n_heads: int, head_dim: int, sp_degree: int, stream=None) -> None:
+    """[p, n_rows, H/p, D] -> [n_rows, H, D] (block g came from rank g); see include/dit_attn.h."""
+    _sp_layout("dit_attn_sp_unpack_heads", ctx, src, dst, n_rows, n_heads, head_dim, sp_degree, stream)
 
 
 def dit_attn_plan(cu_seqlens, n_heads: int, head_dim: int):

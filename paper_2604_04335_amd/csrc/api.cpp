@@ -14,6 +14,7 @@
 #include "attn_fwd.h"
 #include "merge.h"
 #include "plan.h"
+#include "sp_layout.h"
 
 namespace {
 
@@ -340,6 +341,37 @@ int dit_attn_cross_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, c
                               void* out, float* lse, void* stream) {
   if (ctx && !cu_seqlens_k) return fail(ctx, DIT_ATTN_ERR_NULL, "cu_seqlens_k is NULL");
   return forward(ctx, q, k, v, cu_seqlens_q, cu_seqlens_k, n_seqs, n_heads, head_dim, scale, out, lse, stream);
+}
+
+static int sp_layout(dit_attn_ctx* ctx, bool pack, const void* src, void* dst, int64_t n_rows, int32_t n_heads,
+                     int32_t head_dim, int32_t sp_degree, void* stream) {
+  if (!ctx) return DIT_ATTN_ERR_NULL;
+  ctx->error.clear();
+  if (head_dim != 64 && head_dim != 128) return fail(ctx, DIT_ATTN_ERR_HEAD_DIM, "head_dim must be 64 or 128");
+  if (n_heads < 1 || n_heads > 65535) return fail(ctx, DIT_ATTN_ERR_N_HEADS, "n_heads must be in 1..65535");
+  if (sp_degree < 1 || n_heads % sp_degree != 0)
+    return fail(ctx, DIT_ATTN_ERR_N_HEADS, "sp_degree must be >= 1 and divide n_heads");
+  if (n_rows < 0) return fail(ctx, DIT_ATTN_ERR_CU_SEQLENS, "n_rows must be >= 0");
+  if (n_rows == 0) return DIT_ATTN_OK;
+  if (!src || !dst) return fail(ctx, DIT_ATTN_ERR_NULL, "src and dst must be non-NULL");
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u)
+    return fail(ctx, DIT_ATTN_ERR_ALIGN, "src and dst must be 16-byte aligned");
+  DeviceGuard guard;
+  hipError_t e = guard.enter(ctx->device);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+  e = dit::sp_layout_launch(pack, src, dst, n_rows, n_heads, head_dim, sp_degree, ctx->n_cus, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip(ctx, e, "layout kernel launch");
+  return DIT_ATTN_OK;
+}
+
+int dit_attn_sp_pack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int64_t n_rows, int32_t n_heads, int32_t head_dim,
+                           int32_t sp_degree, void* stream) {
+  return sp_layout(ctx, true, src, dst, n_rows, n_heads, head_dim, sp_degree, stream);
+}
+
+int dit_attn_sp_unpack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int64_t n_rows, int32_t n_heads, int32_t head_dim,
+                             int32_t sp_degree, void* stream) {
+  return sp_layout(ctx, false, src, dst, n_rows, n_heads, head_dim, sp_degree, stream);
 }
 
 int dit_attn_merge(dit_attn_ctx* ctx, const void* const* o_parts, const float* const* lse_parts, int32_t n_parts,
