@@ -1,0 +1,118 @@
+"""Pins for the round-scheduler oracle, and parity of the C++ implementation (host code, no GPU needed) with it."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import sched_dp_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "sched_cases.txt")
+T_IMG = [1.0, 1.5, 2.0, 2.5]
+
+
+def _parse_cases():
+    cases = []
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, vids, imgs, exp = [p.strip() for p in line.split("|")]
+        videos = []
+        for v in vids.split(";"):
+            cands = []
+            for c in v.split(","):
+                c = c.strip()
+                if c == "H":
+                    cands.append(orc.VideoCandidate(gpus=0, hold=True))
+                else:
+                    g, l = c.split(":")
+                    cands.append(orc.VideoCandidate(gpus=int(g), laxity=float(l)))
+            videos.append(cands)
+        deadlines = [float(x) for x in imgs.split(";")] if imgs else []
+        ch, b, rec, f = [p.strip() for p in exp.split(";")]
+        cases.append((name, videos, deadlines, [int(x) for x in ch.split(",")], int(b), int(rec), float(f)))
+    return cases
+
+
+@pytest.mark.parametrize("case", _parse_cases(), ids=lambda c: c[0])
+def test_hand_worked_rounds(case):
+    name, videos, deadlines, choice, b, rec, f = case
+    r = orc.solve_round(4, videos, deadlines, 0.0, T_IMG, 4)
+    assert r["feasible"] and r["choice"] == choice and r["video_gpus"] == b
+    assert r["value"][0] == rec and abs(r["value"][1] - f) < 1e-12
+
+
+def test_equations_by_hand():
+    # Eq. 1: deadline 100, now 40, 20 steps of 2.5 s left -> slack 10
+    assert orc.laxity(100.0, 40.0, 20, 2.5) == 10.0
+    # Eq. 5: laxity 3 -> (1, 1/4); laxity -1 -> (0, 1/2); hold -> (0, 0)
+    assert orc.video_score(orc.VideoCandidate(2, 0, 3.0)) == (1, 0.25)
+    assert orc.video_score(orc.VideoCandidate(2, 0, -1.0)) == (0, 0.5)
+    assert orc.video_score(orc.VideoCandidate(0, 0, 9.0, hold=True)) == (0, 0.0)
+    # Eq. 4: two images in one batch of 2 (finishes at 1.5) with deadlines 2 and 4.5: slacks 0.5 and 3 -> 1/1.5 + 1/4
+    assert orc.image_score([2.0, 4.5], 0.0, [0, 0], [2], T_IMG) == (2, 1 / 1.5 + 0.25)
+
+
+def test_edf_batch_hand_cases_and_invariants():
+    # deadlines 3, 1, 2.6, 0.5 (the last cannot be met even alone), one GPU: EDF order 0.5(skip), 1, 2.6, 3.
+    # {1} alone; adding 2.6 makes b = 2 finish at 1.5 > 1 -> no second GPU, left out; same for 3.
+    assert orc.edf_batch([3.0, 1.0, 2.6, 0.5], 0.0, 1, T_IMG, 4) == ([-1, 0, -1, -1], [1])
+    # two GPUs: {1}, then {2.6} opens batch 2 and 3 joins it (b = 2 finishes at 1.5)
+    assert orc.edf_batch([3.0, 1.0, 2.6, 0.5], 0.0, 2, T_IMG, 4) == ([1, 0, 1, -1], [1, 2])
+    # b_max caps a batch even when deadlines are loose; no GPU, no plan
+    assert orc.edf_batch([9.0] * 5, 0.0, 1, T_IMG, 4)[1] == [4]
+    assert orc.edf_batch([9.0] * 5, 0.0, 0, T_IMG, 4) == ([-1] * 5, [])
+    g = np.random.Generator(np.random.PCG64(501))
+    for _ in range(200):
+        n, gpus = int(g.integers(0, 12)), int(g.integers(0, 5))
+        d = list(g.uniform(0.5, 4.0, size=n))
+        batch_of, sizes = orc.edf_batch(d, 0.0, gpus, T_IMG, 4)
+        assert len(sizes) <= gpus and all(1 <= s <= 4 for s in sizes)
+        for i, k in enumerate(batch_of):
+            assert k == -1 or T_IMG[sizes[k] - 1] <= d[i]
+        assert sorted(k for k in batch_of if k >= 0) == sorted(sum(([k] * s for k, s in enumerate(sizes)), []))
+
+
+def _random_instance(g, anchored):
+    N = int(g.choice([2, 4, 8]))
+    G = int(g.integers(0, 5))
+    videos = []
+    for _ in range(G):
+        cands = [orc.VideoCandidate(gpus=0, hold=True)]
+        for p in (1, 2, 4, 8):
+            if p <= N and g.random() < 0.7:
+                mask = 0
+                if anchored:
+                    start = int(g.integers(0, N // p)) * p
+                    mask = ((1 << p) - 1) << start
+                cands.append(orc.VideoCandidate(gpus=p, gpu_mask=mask, laxity=float(np.round(g.normal(1.0, 3.0), 3))))
+        order = g.permutation(len(cands))
+        videos.append([cands[i] for i in order])
+    deadlines = list(np.round(g.uniform(0.5, 4.0, size=int(g.integers(0, 7))), 3))
+    return N, videos, deadlines
+
+
+def test_dp_reaches_the_enumerated_optimum_without_anchoring():
+    g = np.random.Generator(np.random.PCG64(502))
+    for _ in range(300):
+        N, videos, deadlines = _random_instance(g, anchored=False)
+        r = orc.solve_round(N, videos, deadlines, 0.0, T_IMG, 4)
+        best = orc.enumerate_best(N, videos, deadlines, 0.0, T_IMG, 4)
+        assert r["feasible"] and r["value"][0] == best[0] and abs(r["value"][1] - best[1]) < 1e-9
+
+
+def test_dp_plans_are_valid_with_anchoring_and_never_beat_the_optimum():
+    g = np.random.Generator(np.random.PCG64(503))
+    for _ in range(300):
+        N, videos, deadlines = _random_instance(g, anchored=True)
+        r = orc.solve_round(N, videos, deadlines, 0.0, T_IMG, 4)
+        assert r["feasible"]                                # hold is always there
+        mask = 0
+        for j, ci in enumerate(r["choice"]):
+            c = videos[j][ci]
+            assert not (c.gpu_mask & mask)
+            mask |= c.gpu_mask
+        assert sum(videos[j][ci].gpus for j, ci in enumerate(r["choice"])) == r["video_gpus"] <= N
+        assert len(r["image_batch_sizes"]) <= N - r["video_gpus"]
+        assert r["value"] <= orc.enumerate_best(N, videos, deadlines, 0.0, T_IMG, 4)
