@@ -175,6 +175,47 @@ def bench_other(da, torch, ctx, args):
                          "algorithmic_hbm_bytes": int(2 * (sum(q_lens) * 2 + sum(k_lens) * 2) * H * D)}}
 
 
+def bench_sched():
+    """Host-only: time of one round of the paper's Algorithm 1 in the library against the Python oracle (Table 6 of the
+    paper reports 0.24-0.41 ms mean for its solver on an 8-GPU cluster)."""
+    import ctypes
+    import paper_2604_04335_amd as da
+    from oracle import sched_dp_oracle as orc
+    lib = da.load_library()
+    g = np.random.Generator(np.random.PCG64(3001))
+    N, G, n_img, t_img = 8, 16, 64, [1.0, 1.5, 2.0, 2.5]
+    videos = [[(0, 0, 0.0, True)] + [(p, 0, float(g.normal(1, 3)), False) for p in (1, 2, 4, 8)] for _ in range(G)]
+    deadlines = np.ascontiguousarray(g.uniform(0.5, 6.0, size=n_img))
+    flat = [da.SchedCandidate(c[0], c[1], c[2], int(c[3]), 0) for v in videos for c in v]
+    arr = (da.SchedCandidate * len(flat))(*flat)
+    offs = np.arange(0, 5 * G + 1, 5, dtype=np.int32)
+    timg = np.ascontiguousarray(t_img, dtype=np.float64)
+    choice, batch, gpu = np.zeros(G, np.int32), np.zeros(n_img, np.int32), np.zeros(N, np.int32)
+    nb, vg, rec, util = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_double()
+    i32p, f64p = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double)
+    cargs = (N, arr, offs.ctypes.data_as(i32p), G, deadlines.ctypes.data_as(f64p), n_img, 0.0, timg.ctypes.data_as(f64p), 4,
+             choice.ctypes.data_as(i32p), batch.ctypes.data_as(i32p), gpu.ctypes.data_as(i32p), ctypes.byref(nb), ctypes.byref(vg),
+             ctypes.byref(rec), ctypes.byref(util))
+    reps = 20000
+    for _ in range(100):
+        lib.dit_sched_plan_round(*cargs)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        lib.dit_sched_plan_round(*cargs)
+    us = (time.perf_counter() - t0) / reps * 1e6
+    ov = [[orc.VideoCandidate(c[0], c[1], c[2], c[3]) for c in v] for v in videos]
+    t0 = time.perf_counter()
+    for _ in range(50):
+        want = orc.solve_round(N, ov, list(deadlines), 0.0, t_img, 4)
+    oracle_us = (time.perf_counter() - t0) / 50 * 1e6
+    assert want["choice"] == choice.tolist()
+    return {"metric": "round scheduler (Algorithm 1) time per round, microseconds, host", "value": round(us, 2), "unit": "us",
+            "n_gpus": 0, "steps": reps, "warmup": 100, "higher_is_better": False, "data": "synthetic",
+            "config": {"workload": "8 GPUs, 16 videos x 5 candidates, 64 pending images; includes the ctypes call"},
+            "vs_paper_solver_mean_us": [240, 410],
+            "cpu_baseline": {"value": round(oracle_us, 1), "unit": "us", "cores": 1, "kind": "oracle", "sample": "50 rounds of the same instance"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,7 +225,7 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other configurations (reported under per_config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--op", default="attn", choices=["attn", "merge", "cross", "layout"],
+    ap.add_argument("--op", default="attn", choices=["attn", "merge", "cross", "layout", "sched"],
                     help="attn: the denoising-step self-attention (the headline line); merge / cross: one line for the "
                          "partial-result merge kernel (HBM bound) or for cross-attention against text keys")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -193,6 +234,10 @@ def main():
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.op == "sched":
+        print(json.dumps(bench_sched()), flush=True)
+        return
 
     import torch
     import paper_2604_04335_amd as da

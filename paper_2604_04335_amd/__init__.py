@@ -28,6 +28,9 @@ __all__ = [
     "dit_attn_merge",
     "dit_attn_sp_pack_heads",
     "dit_attn_sp_unpack_heads",
+    "dit_sched_laxity",
+    "dit_sched_plan_round",
+    "SchedCandidate",
     "dit_attn_destroy",
     "dit_attn_last_error",
     "dit_attn_plan",
@@ -56,6 +59,12 @@ ERROR_NAMES = {
     -9: "DIT_ATTN_ERR_KERNEL",
     -10: "DIT_ATTN_ERR_PARTS",
 }
+
+
+class SchedCandidate(ctypes.Structure):
+    """dit_sched_candidate of include/dit_sched.h."""
+    _fields_ = [("gpus", ctypes.c_int32), ("gpu_mask", ctypes.c_uint32), ("laxity", ctypes.c_double),
+                ("hold", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class DitAttnError(RuntimeError):
@@ -94,6 +103,12 @@ def load_library() -> ctypes.CDLL:
     for fn in (lib.dit_attn_sp_pack_heads, lib.dit_attn_sp_unpack_heads):
         fn.restype = ctypes.c_int
         fn.argtypes = [vp, vp, vp, i64, i32, i32, i32, vp]
+    lib.dit_sched_laxity.restype = ctypes.c_double
+    lib.dit_sched_laxity.argtypes = [ctypes.c_double, ctypes.c_double, i32, ctypes.c_double]
+    f64p = ctypes.POINTER(ctypes.c_double)
+    lib.dit_sched_plan_round.restype = ctypes.c_int
+    lib.dit_sched_plan_round.argtypes = [i32, ctypes.POINTER(SchedCandidate), i32p, i32, f64p, i32, ctypes.c_double, f64p, i32,
+                                         i32p, i32p, i32p, i32p, i32p, i32p, f64p]
     lib.dit_attn_merge.restype = ctypes.c_int
     lib.dit_attn_merge.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i64, i32, i32, vp, vp, vp]
     lib.dit_attn_last_error.restype = ctypes.c_char_p
@@ -305,3 +320,41 @@ class DitAttention:
             self.close()
         except Exception:
             pass
+
+
+def dit_sched_laxity(deadline: float, t_now: float, steps_remaining: int, t_step: float) -> float:
+    """Eq. 1 of the paper for a configuration; see include/dit_sched.h."""
+    return float(load_library().dit_sched_laxity(float(deadline), float(t_now), int(steps_remaining), float(t_step)))
+
+
+def dit_sched_plan_round(n_gpus: int, videos, image_deadlines, t_now: float, t_img):
+    """One round of the paper's Algorithm 1 (include/dit_sched.h).  videos: per video a sequence of candidates, each a
+    SchedCandidate or a tuple (gpus, gpu_mask, laxity, hold).  Returns a dict with choice, video_gpus, image_batch,
+    image_gpu (one GPU id per image batch), recoverable, utility.  Raises DitAttnError on an error code."""
+    lib = load_library()
+    flat, offs = [], [0]
+    for cands in videos:
+        for c in cands:
+            flat.append(c if isinstance(c, SchedCandidate) else SchedCandidate(int(c[0]), int(c[1]), float(c[2]), int(bool(c[3])), 0))
+        offs.append(len(flat))
+    arr = (SchedCandidate * max(len(flat), 1))(*flat)
+    offs_a = np.asarray(offs, dtype=np.int32)
+    dl = np.ascontiguousarray(image_deadlines, dtype=np.float64)
+    timg = np.ascontiguousarray(t_img, dtype=np.float64)
+    G, n_img = len(videos), int(dl.size)
+    choice = np.zeros(max(G, 1), dtype=np.int32)
+    batch = np.zeros(max(n_img, 1), dtype=np.int32)
+    gpu = np.zeros(max(int(n_gpus), 1), dtype=np.int32)
+    nb, vg, rec = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    util = ctypes.c_double(0.0)
+    i32p, f64p = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double)
+    rc = lib.dit_sched_plan_round(int(n_gpus), arr, offs_a.ctypes.data_as(i32p), G,
+                                  dl.ctypes.data_as(f64p) if n_img else None, n_img, float(t_now),
+                                  timg.ctypes.data_as(f64p), int(timg.size), choice.ctypes.data_as(i32p),
+                                  batch.ctypes.data_as(i32p), gpu.ctypes.data_as(i32p), ctypes.byref(nb), ctypes.byref(vg),
+                                  ctypes.byref(rec), ctypes.byref(util))
+    if rc != 0:
+        raise DitAttnError(rc, "dit_sched_plan_round")
+    return {"choice": choice[:G].tolist(), "video_gpus": int(vg.value), "image_batch": batch[:n_img].tolist(),
+            "image_gpu": gpu[:int(nb.value)].tolist(), "n_batches": int(nb.value), "recoverable": int(rec.value),
+            "utility": float(util.value)}

@@ -13,16 +13,22 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "dit_attn.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(dit_attn_[a-z_]+)\s*\(", text)))
+    """Every function that any header under include/ declares."""
+    import glob
+    names = set()
+    for path in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        text = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
+        names |= set(re.findall(r"\b(dit_(?:attn|sched)_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_loads_and_exports_every_declared_symbol():
     lib = da.load_library()
     names = _declared_symbols()
     assert {"dit_attn_create", "dit_attn_varlen_fwd", "dit_attn_destroy", "dit_attn_last_error",
-            "dit_attn_plan", "dit_attn_version"} <= set(names)
+            "dit_attn_plan", "dit_attn_version", "dit_attn_varlen_fwd_lse", "dit_attn_cross_varlen_fwd", "dit_attn_merge",
+            "dit_attn_sp_pack_heads", "dit_attn_sp_unpack_heads", "dit_attn_set_kernel", "dit_attn_last_launch_clock",
+            "dit_sched_plan_round", "dit_sched_laxity"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     assert "gfx950" in da.dit_attn_version()
