@@ -225,6 +225,8 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other configurations (reported under per_config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--split-kv", type=int, default=1,
+                    help="let small packs split every sequence's keys into up to this many chunks (dit_attn_set_split_kv)")
     ap.add_argument("--op", default="attn", choices=["attn", "merge", "cross", "layout", "sched"],
                     help="attn: the denoising-step self-attention (the headline line); merge / cross: one line for the "
                          "partial-result merge kernel (HBM bound) or for cross-attention against text keys")
@@ -257,6 +259,7 @@ def main():
                           "launches": 3}), flush=True)
         return
     ctx = da.dit_attn_create(0)
+    da.dit_attn_set_split_kv(ctx, args.split_kv)
     if args.op != "attn":
         print(json.dumps(bench_other(da, torch, ctx, args)), flush=True)
         da.dit_attn_destroy(ctx)
@@ -297,6 +300,7 @@ def main():
             "total_tokens": w.total_tokens,
             "tflop_per_call": round(flops / 1e12, 4),
             "seed": w.seed,
+            "split_kv": args.split_kv,
         },
         "pct_of_mfma_peak": round(100.0 * tflops / MFMA_BF16_PEAK_TFLOPS, 2),
         "step_ms_min": round(float(np.min(per)), 4),

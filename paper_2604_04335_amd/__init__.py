@@ -35,6 +35,7 @@ __all__ = [
     "dit_attn_last_error",
     "dit_attn_plan",
     "dit_attn_set_kernel",
+    "dit_attn_set_split_kv",
     "dit_attn_last_launch_clock",
     "KERNEL_AUTO",
     "KERNEL_128",
@@ -113,6 +114,8 @@ def load_library() -> ctypes.CDLL:
     lib.dit_attn_merge.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i64, i32, i32, vp, vp, vp]
     lib.dit_attn_last_error.restype = ctypes.c_char_p
     lib.dit_attn_last_error.argtypes = [vp]
+    lib.dit_attn_set_split_kv.restype = ctypes.c_int
+    lib.dit_attn_set_split_kv.argtypes = [vp, ctypes.c_int]
     lib.dit_attn_set_kernel.restype = ctypes.c_int
     lib.dit_attn_set_kernel.argtypes = [vp, ctypes.c_int]
     lib.dit_attn_last_launch_clock.restype = ctypes.c_int
@@ -163,6 +166,13 @@ KERNEL_AUTO, KERNEL_128, KERNEL_PINGPONG, KERNEL_WIDE = -1, 0, 1, 2
 def dit_attn_set_kernel(ctx, kernel: int) -> None:
     """Force one of the library's kernels for later calls on `ctx` (KERNEL_AUTO: chosen per pack)."""
     rc = load_library().dit_attn_set_kernel(ctypes.c_void_p(ctx), int(kernel))
+    if rc != 0:
+        raise DitAttnError(rc, dit_attn_last_error(ctx))
+
+
+def dit_attn_set_split_kv(ctx, max_splits: int) -> None:
+    """Allow small packs to split every sequence's keys into up to max_splits chunks (1 = off); see include/dit_attn.h."""
+    rc = load_library().dit_attn_set_split_kv(ctypes.c_void_p(ctx), int(max_splits))
     if rc != 0:
         raise DitAttnError(rc, dit_attn_last_error(ctx))
 

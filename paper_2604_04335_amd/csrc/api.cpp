@@ -3,7 +3,10 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <climits>
 #include <cmath>
+#include <cstdint>
 #include <cstdio>
 #include <cstring>
 #include <memory>
@@ -24,6 +27,7 @@ struct CachedPlan {
   int32_t n_heads = 0;
   int32_t head_dim = 0;
   dit::AttnKernel kernel = dit::AttnKernel::kIndependent128;
+  int32_t n_splits = 1;  // key chunks per sequence (split-KV); part of the key
   std::vector<dit::WorkItem> host_items;  // kept alive: source of the stream-ordered upload
   dit::WorkItem* dev_items = nullptr;
   uint64_t last_use = 0;
@@ -43,6 +47,9 @@ struct dit_attn_ctx {
   uint32_t* sync = nullptr;     // device, 8 words: work counters (zero between launches) and the last launch's clock sample
   uint64_t tick = 0;
   int force_kernel = -1;        // -1: chosen per pack; else a dit::AttnKernel value (dit_attn_set_kernel)
+  int max_splits = 1;           // split-KV: at most this many key chunks per sequence (dit_attn_set_split_kv); 1 = off
+  float* workspace = nullptr;   // split-KV partial results and their lse
+  size_t workspace_bytes = 0;
   std::vector<std::unique_ptr<CachedPlan>> plans;
   std::string error;
 };
@@ -157,6 +164,7 @@ void dit_attn_destroy(dit_attn_ctx* ctx) {
     for (auto& p : ctx->plans)
       if (p->dev_items) (void)hipFree(p->dev_items);
     if (ctx->sync) (void)hipFree(ctx->sync);
+    if (ctx->workspace) (void)hipFree(ctx->workspace);
   }
   (void)hipGetLastError();
   delete ctx;
@@ -167,6 +175,14 @@ int dit_attn_set_kernel(dit_attn_ctx* ctx, int kernel) {
   if (kernel < -1 || kernel > static_cast<int>(dit::AttnKernel::kWide256))
     return fail(ctx, DIT_ATTN_ERR_KERNEL, "kernel must be -1 (automatic), 0 (128-row), 1 (ping-pong) or 2 (wide)");
   ctx->force_kernel = kernel;
+  return DIT_ATTN_OK;
+}
+
+int dit_attn_set_split_kv(dit_attn_ctx* ctx, int max_splits) {
+  if (!ctx) return DIT_ATTN_ERR_NULL;
+  if (max_splits < 1 || max_splits > dit::kMaxMergeParts)
+    return fail(ctx, DIT_ATTN_ERR_PARTS, "max_splits must be in 1.." + std::to_string(dit::kMaxMergeParts));
+  ctx->max_splits = max_splits;
   return DIT_ATTN_OK;
 }
 
@@ -246,8 +262,26 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
   const size_t cu_n = static_cast<size_t>(n_seqs) + 1;
   const dit::AttnKernel kernel = ctx->force_kernel >= 0 ? static_cast<dit::AttnKernel>(ctx->force_kernel)
                                                         : dit::attn_fwd_select(cu_seqlens, n_seqs, n_heads, ctx->n_cus);
+  // Split-KV (opt-in): a pack of the 128-row kernel with fewer items than compute units cuts every sequence's keys into
+  // chunks of at least four key tiles, as many as it takes to reach two items per compute unit, and merges the parts.
+  int32_t n_splits = 1;
+  if (ctx->max_splits > 1 && kernel == dit::AttnKernel::kIndependent128) {
+    const int32_t* ck = cu_k ? cu_k : cu_seqlens;
+    int64_t items = 0, min_tiles = INT64_MAX;
+    for (int32_t i = 0; i < n_seqs; ++i) {
+      const int64_t lq = cu_seqlens[i + 1] - cu_seqlens[i], lk = ck[i + 1] - ck[i];
+      if (lq == 0 || lk == 0) continue;
+      items += (lq + 127) / 128 * n_heads;
+      min_tiles = std::min<int64_t>(min_tiles, (lk + 63) / 64);
+    }
+    // Measured on MI355X: the two extra launches (fill, merge) cost about as much as is gained below ~3000 keys.
+    if (items > 0 && items < ctx->n_cus && min_tiles >= 48) {
+      const int64_t want = (2 * static_cast<int64_t>(ctx->n_cus) + items - 1) / items;
+      n_splits = static_cast<int32_t>(std::max<int64_t>(1, std::min<int64_t>({want, ctx->max_splits, min_tiles / 4})));
+    }
+  }
   for (auto& p : ctx->plans) {
-    if (p->n_heads == n_heads && p->head_dim == head_dim && p->kernel == kernel && p->cu.size() == cu_n &&
+    if (p->n_heads == n_heads && p->head_dim == head_dim && p->kernel == kernel && p->n_splits == n_splits && p->cu.size() == cu_n &&
         p->cu_k.size() == (cu_k ? cu_n : 0) && std::memcmp(p->cu.data(), cu_seqlens, cu_n * sizeof(int32_t)) == 0 &&
         (!cu_k || std::memcmp(p->cu_k.data(), cu_k, cu_n * sizeof(int32_t)) == 0)) {
       plan = p.get();
@@ -263,7 +297,9 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
       np->n_heads = n_heads;
       np->head_dim = head_dim;
       np->kernel = kernel;
-      dit::plan_build_cross(cu_seqlens, cu_k ? cu_k : cu_seqlens, n_seqs, n_heads, dit::attn_fwd_block_m(np->kernel), np->host_items);
+      np->n_splits = n_splits;
+      dit::plan_build_cross(cu_seqlens, cu_k ? cu_k : cu_seqlens, n_seqs, n_heads, dit::attn_fwd_block_m(np->kernel), np->host_items,
+                            n_splits);
     } catch (...) {
       return fail(ctx, DIT_ATTN_ERR_HIP, "out of host memory while building the work-list");
     }
@@ -303,7 +339,30 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
   const int64_t max_grid = static_cast<int64_t>(ctx->n_cus) * dit::attn_fwd_wgs_per_cu(plan->kernel);
   const int grid = static_cast<int>(n_items < max_grid ? n_items : max_grid);
 
+  const int64_t total_q = cu_seqlens[n_seqs];
+  if (n_splits > 1) {
+    const size_t need = static_cast<size_t>(n_splits) * static_cast<size_t>(total_q) * static_cast<size_t>(n_heads) *
+                        (static_cast<size_t>(head_dim) + 1) * sizeof(float);
+    if (need > ctx->workspace_bytes) {
+      if (ctx->workspace) (void)hipFree(ctx->workspace);  // waits for the device: no kernel still uses it
+      ctx->workspace = nullptr;
+      ctx->workspace_bytes = 0;
+      e = hipMalloc(reinterpret_cast<void**>(&ctx->workspace), need);
+      if (e != hipSuccess) return fail_hip(ctx, e, "hipMalloc(split-KV workspace)");
+      ctx->workspace_bytes = need;
+    }
+  }
+  float* part_out = n_splits > 1 ? ctx->workspace : nullptr;
+  float* part_lse = n_splits > 1 ? ctx->workspace + static_cast<size_t>(n_splits) * total_q * n_heads * head_dim : nullptr;
+  if (n_splits > 1) {  // a sequence with fewer chunks than n_splits leaves parts unwritten: their weight must be 0
+    e = dit::fill_neg_inf_launch(part_lse, static_cast<int64_t>(n_splits) * total_q * n_heads, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "fill kernel launch");
+  }
+
   dit::AttnParams p;
+  p.part_out = part_out;
+  p.part_lse = part_lse;
+  p.part_rows = total_q;
   p.q = q;
   p.k = k;
   p.v = v;
@@ -317,6 +376,20 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
   p.negate = scale < 0.f ? 1 : 0;
   e = dit::attn_fwd_launch(p, plan->kernel, head_dim, grid, s);
   if (e != hipSuccess) return fail_hip(ctx, e, "kernel launch");
+  if (n_splits > 1) {
+    dit::MergeParams m{};
+    for (int32_t i = 0; i < n_splits; ++i) {
+      m.o[i] = part_out + static_cast<size_t>(i) * total_q * n_heads * head_dim;
+      m.lse[i] = part_lse + static_cast<size_t>(i) * total_q * n_heads;
+    }
+    m.out = out;
+    m.lse_out = lse;
+    m.chunks_per_row = head_dim * 2 / 16;
+    m.n_chunks = total_q * n_heads * m.chunks_per_row;
+    m.in_f32 = 1;
+    e = dit::merge_launch(m, n_splits, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "merge kernel launch");
+  }
   return DIT_ATTN_OK;
 }
 

@@ -411,7 +411,7 @@ __device__ __forceinline__ void launch_clock_end(const AttnParams& p, const Laun
 
 // Work item fields, wave-uniform.
 struct ItemU {
-  int q_start, kv_start, kv_len, head, q_rows;
+  int q_start, kv_start, kv_len, head, q_rows, part;
 };
 __device__ __forceinline__ ItemU fetch_item(const WorkItem* items, uint32_t idx) {
   const WorkItem it = items[idx];
@@ -421,7 +421,8 @@ __device__ __forceinline__ ItemU fetch_item(const WorkItem* items, uint32_t idx)
   u.kv_len = __builtin_amdgcn_readfirstlane(it.kv_len);
   const int rh = __builtin_amdgcn_readfirstlane(it.rows_head);
   u.head = rh & 0xFFFF;
-  u.q_rows = (rh >> 16) & 0xFFFF;
+  u.q_rows = (rh >> 16) & 0xFFF;
+  u.part = (rh >> 28) & 0xF;
   return u;
 }
 
@@ -445,6 +446,22 @@ __device__ __forceinline__ void store_out(const AttnParams& p, const Lane<T>& L,
                                           int64_t head_off, int qrow, bool row_valid, const f32x16 (&o)[T::NDB],
                                           float l_run, float m_ref) {
   const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (row_valid && p.part_out != nullptr) {
+    // split-KV: this item saw one chunk of the keys; its normalised result and lse go to the workspace in fp32
+    const float inv = 1.0f / l_tot;
+    const int64_t rh = ((int64_t)it.part * p.part_rows + it.q_start + qrow) * p.n_heads + it.head;
+    float* optr = p.part_out + rh * T::D + L.hh * 4;
+#pragma unroll
+    for (int db = 0; db < T::NDB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+        *reinterpret_cast<f32x4*>(optr + 32 * db + 8 * g) =
+            f32x4{o[db][4 * g + 0] * inv, o[db][4 * g + 1] * inv, o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv};
+      }
+    if (L.hh == 0) p.part_lse[rh] = 0.69314718055994530942f * (m_ref * p.c_log2 + __builtin_amdgcn_logf(l_tot));
+    return;
+  }
   if (row_valid) {
     const float inv = 1.0f / l_tot;
     char* optr = static_cast<char*>(p.out) + (int64_t)(it.q_start + qrow) * row_stride_b + head_off + L.hh * 8;

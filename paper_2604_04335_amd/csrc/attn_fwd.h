@@ -12,6 +12,10 @@ struct AttnParams {
   const void* k;            // bf16 [Tk, H, D] (Tk = Tq and the same boundaries for self-attention)
   const void* v;
   void* out;                // bf16 [T, H, D]
+  float* part_out;          // split-KV: fp32 [n_parts, Tq, H, D] workspace for normalised partial results, else nullptr;
+                            // then out is not written and part_lse (fp32 [n_parts, Tq, H]) takes every part's lse
+  float* part_lse;
+  int64_t part_rows;        // Tq
   float* lse;               // fp32 [T, H] or nullptr: natural-log sum of exp(scale * score) of every (query row, head)
   const WorkItem* items;    // device work-list
   uint32_t* sync;           // device, 8 words (8-byte aligned): [0] items taken so far, [1] workgroups finished,

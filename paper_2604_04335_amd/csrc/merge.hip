@@ -23,7 +23,7 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));  // round to nearest even
 }
 
-template <int P>
+template <int P, bool F32>
 __global__ void __launch_bounds__(256) merge_kernel(MergeParams p) {
   const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;  // 16-byte chunk of the output
   if (e >= p.n_chunks) return;
@@ -45,14 +45,25 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeParams p) {
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < P; ++i) {
-    const u32x4 x = reinterpret_cast<const u32x4*>(p.o[i])[e];
     const float wi = w[i] * inv;
+    float xv[8];
+    if (F32) {
+      typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+      const f32x4* src = reinterpret_cast<const f32x4*>(p.o[i]) + 2 * e;
+      const f32x4 x0 = src[0], x1 = src[1];
+      xv[0] = x0[0]; xv[1] = x0[1]; xv[2] = x0[2]; xv[3] = x0[3];
+      xv[4] = x1[0]; xv[5] = x1[1]; xv[6] = x1[2]; xv[7] = x1[3];
+    } else {
+      const u32x4 x = reinterpret_cast<const u32x4*>(p.o[i])[e];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      // a weight of exactly 0 must also silence a non-finite value of a part that had no keys
-      acc[2 * j] += wi == 0.f ? 0.f : wi * bf16_lo(x[j]);
-      acc[2 * j + 1] += wi == 0.f ? 0.f : wi * bf16_hi(x[j]);
+      for (int j = 0; j < 4; ++j) {
+        xv[2 * j] = bf16_lo(x[j]);
+        xv[2 * j + 1] = bf16_hi(x[j]);
+      }
     }
+    // a weight of exactly 0 must also silence a non-finite value of a part that had no keys
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += wi == 0.f ? 0.f : wi * xv[j];
   }
   u32x4 y;
 #pragma unroll
@@ -67,14 +78,38 @@ hipError_t merge_launch(const MergeParams& p, int n_parts, hipStream_t stream) {
   if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
   const dim3 grid((unsigned)blocks), block(256);
   switch (n_parts) {
-    case 1: hipLaunchKernelGGL(merge_kernel<1>, grid, block, 0, stream, p); break;
-    case 2: hipLaunchKernelGGL(merge_kernel<2>, grid, block, 0, stream, p); break;
-    case 3: hipLaunchKernelGGL(merge_kernel<3>, grid, block, 0, stream, p); break;
-    case 4: hipLaunchKernelGGL(merge_kernel<4>, grid, block, 0, stream, p); break;
-    case 5: hipLaunchKernelGGL(merge_kernel<5>, grid, block, 0, stream, p); break;
-    case 6: hipLaunchKernelGGL(merge_kernel<6>, grid, block, 0, stream, p); break;
-    case 7: hipLaunchKernelGGL(merge_kernel<7>, grid, block, 0, stream, p); break;
-    case 8: hipLaunchKernelGGL(merge_kernel<8>, grid, block, 0, stream, p); break;
+    case 1:
+      if (p.in_f32) hipLaunchKernelGGL((merge_kernel<1, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((merge_kernel<1, false>), grid, block, 0, stream, p);
+      break;
+    case 2:
+      if (p.in_f32) hipLaunchKernelGGL((merge_kernel<2, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((merge_kernel<2, false>), grid, block, 0, stream, p);
+      break;
+    case 3:
+      if (p.in_f32) hipLaunchKernelGGL((merge_kernel<3, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((merge_kernel<3, false>), grid, block, 0, stream, p);
+      break;
+    case 4:
+      if (p.in_f32) hipLaunchKernelGGL((merge_kernel<4, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((merge_kernel<4, false>), grid, block, 0, stream, p);
+      break;
+    case 5:
+      if (p.in_f32) hipLaunchKernelGGL((merge_kernel<5, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((merge_kernel<5, false>), grid, block, 0, stream, p);
+      break;
+    case 6:
+      if (p.in_f32) hipLaunchKernelGGL((merge_kernel<6, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((merge_kernel<6, false>), grid, block, 0, stream, p);
+      break;
+    case 7:
+      if (p.in_f32) hipLaunchKernelGGL((merge_kernel<7, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((merge_kernel<7, false>), grid, block, 0, stream, p);
+      break;
+    case 8:
+      if (p.in_f32) hipLaunchKernelGGL((merge_kernel<8, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((merge_kernel<8, false>), grid, block, 0, stream, p);
+      break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -87,6 +122,19 @@ __global__ void __launch_bounds__(256) fill_rows_kernel(u32x4* out, float* lse, 
   const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (e < n_chunks) out[chunk0 + e] = u32x4{0u, 0u, 0u, 0u};
   if (lse != nullptr && e < n_lse) lse[lse0 + e] = -__builtin_inff();
+}
+
+__global__ void __launch_bounds__(256) fill_neg_inf_kernel(float* p, int64_t n) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e < n) p[e] = -__builtin_inff();
+}
+
+hipError_t fill_neg_inf_launch(float* p, int64_t n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  const int64_t blocks = (n + 255) / 256;
+  if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fill_neg_inf_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p, n);
+  return hipGetLastError();
 }
 
 hipError_t fill_rows_launch(void* out, float* lse, int64_t row0, int64_t n_rows, int n_heads, int head_dim, hipStream_t stream) {

@@ -19,7 +19,7 @@ void plan_build(const int32_t* cu, int32_t n_seqs, int32_t n_heads, int32_t bloc
 }
 
 void plan_build_cross(const int32_t* cu_q, const int32_t* cu_k, int32_t n_seqs, int32_t n_heads, int32_t block_m,
-                      std::vector<WorkItem>& items) {
+                      std::vector<WorkItem>& items, int32_t n_splits, int32_t block_n) {
   items.clear();
   // Sequence order: by number of keys (the cost of one item), most first; ties keep pack order (stable).
   std::vector<int32_t> order(static_cast<size_t>(n_seqs));
@@ -30,17 +30,22 @@ void plan_build_cross(const int32_t* cu_q, const int32_t* cu_k, int32_t n_seqs, 
   size_t total = 0;
   for (int32_t i = 0; i < n_seqs; ++i) {
     const int64_t len = cu_q[i + 1] - cu_q[i];
-    if (cu_k[i + 1] > cu_k[i]) total += static_cast<size_t>((len + block_m - 1) / block_m) * static_cast<size_t>(n_heads);
+    if (cu_k[i + 1] > cu_k[i])
+      total += static_cast<size_t>((len + block_m - 1) / block_m) * static_cast<size_t>(n_heads) * static_cast<size_t>(n_splits);
   }
   items.reserve(total);
   for (int32_t s : order) {
     const int32_t q0 = cu_q[s], q_len = cu_q[s + 1] - cu_q[s];
     const int32_t k0 = cu_k[s], k_len = cu_k[s + 1] - cu_k[s];
     if (q_len == 0 || k_len == 0) continue;
+    const int32_t tiles = (k_len + block_n - 1) / block_n;
+    const int32_t tiles_per_part = (tiles + n_splits - 1) / n_splits;
+    const int32_t chunk = tiles_per_part * block_n;
     for (int32_t h = 0; h < n_heads; ++h) {
       for (int32_t m0 = 0; m0 < q_len; m0 += block_m) {
         const int32_t rows = std::min(block_m, q_len - m0);
-        items.push_back(WorkItem{q0 + m0, k0, k_len, (rows << 16) | h});
+        for (int32_t part = 0, kb = 0; kb < k_len; ++part, kb += chunk)
+          items.push_back(WorkItem{q0 + m0, k0 + kb, std::min(chunk, k_len - kb), (part << 28) | (rows << 16) | h});
       }
     }
   }

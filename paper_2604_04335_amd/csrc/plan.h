@@ -16,7 +16,7 @@ struct WorkItem {
   int32_t q_start;    // first global query row of the tile
   int32_t kv_start;   // first global key row (start of the tile's sequence)
   int32_t kv_len;     // keys in the sequence
-  int32_t rows_head;  // (q_rows << 16) | head, q_rows in 1..block_m
+  int32_t rows_head;  // (part << 28) | (q_rows << 16) | head, q_rows in 1..block_m, part = index of the key chunk (split-KV)
 };
 static_assert(sizeof(WorkItem) == 16, "WorkItem must be 16 bytes");
 
@@ -34,6 +34,10 @@ void plan_build(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int3
 // no query rows or no key rows contribute no items (the caller zeroes the output rows of the latter).  Sequences with
 // the most keys come first.
 void plan_build_cross(const int32_t* cu_q, const int32_t* cu_k, int32_t n_seqs, int32_t n_heads, int32_t block_m,
-                      std::vector<WorkItem>& items);
+                      std::vector<WorkItem>& items, int32_t n_splits = 1, int32_t block_n = 64);
+
+// With n_splits > 1 (split-KV, for packs with fewer items than compute units) the keys of every sequence are cut into
+// at most n_splits chunks of whole key tiles (block_n keys), and every (query tile, head) becomes one item per chunk:
+// kv_start / kv_len describe the chunk, part its index.  The parts are combined by the merge kernel.
 
 }  // namespace dit

@@ -210,3 +210,76 @@ def test_new_entry_points_reject_bad_arguments(ctx):
     assert e.value.code == -2
     da.dit_attn_merge(ctx, [out], [lse], 0, 2, 64, out, None, _stream())  # nothing to do
     torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- split-KV
+
+@pytest.mark.parametrize("lens,H,D,max_splits", [
+    ([4096], 4, 64, 8),             # 128 items of 128 rows -> 4 chunks of 1024 keys
+    ([3100, 3073, 5000], 2, 128, 8),  # ragged: chunks of whole tiles, short last chunks, sequences with different chunk counts
+    ([6145], 1, 128, 3),
+    ([3500], 3, 64, 2),
+])
+def test_split_kv_matches_oracle_and_unsplit_result(ctx, lens, H, D, max_splits):
+    w = make_custom(lens, H, D, seed=48)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    base = torch.empty_like(q)
+    da.dit_attn_varlen_fwd(ctx, q, k, v, w.cu_seqlens, H, D, w.scale, base, _stream())
+    SENT = 0x7FC1
+    buf = torch.full((q.shape[0] + 128, H, D), SENT, dtype=torch.int16, device="cuda")
+    out = buf[64:64 + q.shape[0]].view(torch.bfloat16)
+    lse = torch.full((q.shape[0], H), float("nan"), dtype=torch.float32, device="cuda")
+    da.dit_attn_set_split_kv(ctx, max_splits)
+    try:
+        da.dit_attn_varlen_fwd_lse(ctx, q, k, v, w.cu_seqlens, H, D, w.scale, out, lse, _stream())
+        out2 = torch.empty_like(q)
+        da.dit_attn_varlen_fwd(ctx, q, k, v, w.cu_seqlens, H, D, w.scale, out2, _stream())   # same plan from the cache, no lse
+    finally:
+        da.dit_attn_set_split_kv(ctx, 1)
+    torch.cuda.synchronize()
+    assert bool((buf[:64] == SENT).all()) and bool((buf[64 + q.shape[0]:] == SENT).all())
+    ref_o, ref_l = orc.attention_varlen_lse(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    assert_parity(to_bits(out), ref_o, "split-KV")
+    assert np.max(np.abs(lse.cpu().numpy() - ref_l)) <= LSE_TOL
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+    # against the unsplit kernel: the same result up to the rounding of different summation orders
+    d = widen(to_bits(out)) - widen(to_bits(base))
+    assert np.max(np.abs(d)) <= MAX_ABS_TOL
+    assert not torch.equal(out.view(torch.int16), base.view(torch.int16))   # the split path did run
+    # after switching it off again the unsplit bits are back
+    again = torch.empty_like(q)
+    da.dit_attn_varlen_fwd(ctx, q, k, v, w.cu_seqlens, H, D, w.scale, again, _stream())
+    torch.cuda.synchronize()
+    assert torch.equal(again.view(torch.int16), base.view(torch.int16))
+
+
+def test_split_kv_leaves_large_packs_alone_and_rejects_bad_counts(ctx):
+    w = make_custom([8192, 300], 8, 64, seed=49)   # enough items: no split, bits unchanged
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    a, b = torch.empty_like(q), torch.empty_like(q)
+    da.dit_attn_varlen_fwd(ctx, q, k, v, w.cu_seqlens, 8, 64, w.scale, a, _stream())
+    da.dit_attn_set_split_kv(ctx, 8)
+    try:
+        da.dit_attn_varlen_fwd(ctx, q, k, v, w.cu_seqlens, 8, 64, w.scale, b, _stream())
+    finally:
+        da.dit_attn_set_split_kv(ctx, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    for bad in (0, 9):
+        with pytest.raises(da.DitAttnError) as e:
+            da.dit_attn_set_split_kv(ctx, bad)
+        assert e.value.code == -10
+
+
+def test_split_kv_cross_attention(ctx):
+    w = make_cross([600, 100], [5000, 3072], 2, 128, seed=50)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    out = torch.empty_like(q)
+    da.dit_attn_set_split_kv(ctx, 4)
+    try:
+        da.dit_attn_cross_varlen_fwd(ctx, q, k, v, w.cu_seqlens_q, w.cu_seqlens_k, 2, 128, w.scale, out, None, _stream())
+    finally:
+        da.dit_attn_set_split_kv(ctx, 1)
+    torch.cuda.synchronize()
+    ref_o, _ = orc.attention_cross_varlen(w.q, w.k, w.v, w.cu_seqlens_q, w.cu_seqlens_k, w.scale)
+    assert_parity(to_bits(out), ref_o, "split-KV cross-attention")
