@@ -377,8 +377,12 @@ __device__ __forceinline__ void wait_loads_but() { asm volatile("s_waitcnt vmcnt
 // reads address are not written by anyone before the next barrier.
 __device__ __forceinline__ void phase_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-// Work distribution: thread 0 of a workgroup takes the next list index; indices at or past n_items end the workgroup.
-__device__ __forceinline__ uint32_t take_item(const AttnParams& p) { return atomicAdd(&p.sync[0], 1u); }
+// Work distribution: workgroup b starts with list index b; further indices come from one atomic counter (thread 0
+// of a workgroup), offset by the grid size; indices at or past n_items end the workgroup.  A workgroup asks for its
+// next index only towards the end of the current item (two tiles before it ends): asking earlier hides no more latency
+// and takes an item away from workgroups that become idle before this one gets to it (with one item per workgroup and
+// the request made at the start of an item, the first workgroups to start took two items each and the last none).
+__device__ __forceinline__ uint32_t take_item(const AttnParams& p) { return gridDim.x + atomicAdd(&p.sync[0], 1u); }
 // After the item loop: the last workgroup to get here clears both words for the next launch.
 __device__ __forceinline__ void finish_workgroup(const AttnParams& p) {
   __threadfence();

@@ -23,17 +23,16 @@ attn_fwd_kernel(AttnParams p) {
   Lane<T> L;
   L.init(tid, row_stride_b);
 
-  // The index of the next item is fetched one item ahead into the slot of the other parity; the barriers
-  // inside an item (at least two) make it visible to every wave before it is read.
-  if (tid == 0) s_item[0] = take_item(p);
+  // The index of the next item is requested towards the end of an item, into the slot of the other parity; a barrier
+  // between that write and the end of the item makes it visible to every wave before it is read.
+  if (tid == 0) s_item[0] = blockIdx.x;
   wg_barrier();
   int par = 0;
 
   for (;;) {
     const uint32_t item_idx = __builtin_amdgcn_readfirstlane(s_item[par]);
     if (item_idx >= p.n_items) break;
-    if (tid == 0) s_item[par ^ 1] = take_item(p);
-    par ^= 1;
+    par ^= 1;  // the next index goes to s_item[par], see below
     const ItemCtx<T> X = begin_item<T>(p, L, item_idx, row_stride_b);
     const int kv_len = X.it.kv_len, nt = X.nt;
 
@@ -58,11 +57,13 @@ attn_fwd_kernel(AttnParams p) {
     int ka[T::NKS], va[T::NDB];  // operand addresses in the buffers of the current tile's parity
     L.operand_addrs((uint32_t)(uintptr_t)smem, (uint32_t)(uintptr_t)smem, ka, va);
 
+    if (nt == 1 && tid == 0) s_item[par] = take_item(p);  // visible after the barrier below
     for (int t = 0; t < nt; ++t) {
       // Tile t has landed (this wave's loads), and after the barrier everyone's; everyone is also done
       // reading the other buffers (tile t-1), so they can be refilled with tile t+1 while tile t is used.
       wait_loads();
       wg_barrier();
+      if (t + 2 == nt && tid == 0) s_item[par] = take_item(p);  // visible after the barrier of the last tile
       if (t + 1 < nt) load_tile(t + 1);
       mfma_stream<T, false, 0, T::NQK, kPrefetch>(smem, va, ka, pb, qf, o, s);
       if (t + 1 < nt) {
@@ -116,17 +117,16 @@ attn_fwd_pp_kernel(AttnParams p) {
   L.init(tid, row_stride_b);
   const int group = L.wave >> 2;
 
-  // The index of the next item is fetched one item ahead into the slot of the other parity; the barriers
-  // inside an item (at least three) make it visible to every wave before it is read.
-  if (tid == 0) s_item[0] = take_item(p);
+  // The index of the next item is requested towards the end of an item, into the slot of the other parity; a barrier
+  // between that write and the end of the item makes it visible to every wave before it is read.
+  if (tid == 0) s_item[0] = blockIdx.x;
   wg_barrier();
   int par = 0;
 
   for (;;) {
     const uint32_t item_idx = __builtin_amdgcn_readfirstlane(s_item[par]);
     if (item_idx >= p.n_items) break;
-    if (tid == 0) s_item[par ^ 1] = take_item(p);
-    par ^= 1;
+    par ^= 1;  // the next index goes to s_item[par], see below
     const ItemCtx<T> X = begin_item<T>(p, L, item_idx, row_stride_b);
     const int kv_len = X.it.kv_len, nt = X.nt;
 
@@ -177,8 +177,10 @@ attn_fwd_pp_kernel(AttnParams p) {
     for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
     wg_barrier();
 
+    if (nt == 1 && tid == 0) s_item[par] = take_item(p);  // two barriers follow in the last tile
     for (int t = 0; t + 1 < nt; ++t) {
       // ---- vector phase: softmax(t), a full tile
+      if (t + 2 == nt && tid == 0) s_item[par] = take_item(p);
       if (group == 1) load_pair_all(t + 1);
       tile_softmax<T, false>(s, L.hh, TailRows{0, T::BN}, c, pb, o, m_ref, l_run);
       wg_barrier();

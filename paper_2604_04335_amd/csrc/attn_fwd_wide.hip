@@ -260,15 +260,14 @@ attn_fwd_wide_kernel(AttnParams p) {
   Lane<T> L;
   L.init(tid, row_stride_b);
 
-  if (tid == 0) s_item[0] = take_item(p);
+  if (tid == 0) s_item[0] = blockIdx.x;
   wg_barrier();
   int par = 0;
 
   for (;;) {
     const uint32_t item_idx = __builtin_amdgcn_readfirstlane(s_item[par]);
     if (item_idx >= p.n_items) break;
-    if (tid == 0) s_item[par ^ 1] = take_item(p);
-    par ^= 1;
+    par ^= 1;  // the next index goes to s_item[par] during the item's last step (a barrier follows)
     const ItemU it = fetch_item(p.items, item_idx);
     const int kv_len = it.kv_len;
     const int nt = (kv_len + T::BN - 1) / T::BN;
@@ -379,7 +378,9 @@ attn_fwd_wide_kernel(AttnParams p) {
     finish_max();
 
     // One step: scores of tile t are in `cur`; leaves those of tile t+1 in `nxt`.
+    if (nt == 1 && tid == 0) s_item[par] = take_item(p);
     auto step = [&](f32x16 (&cur)[2][T::NKB], f32x16 (&nxt)[2][T::NKB], int t) {
+      if (t + 2 == nt && tid == 0) s_item[par] = take_item(p);
       lsum[0] = 0.f;
       lsum[1] = 0.f;
       // Loads of the pair L(t+3) = {K(t+4), V(t+3)}; nt >= 2 here, so every tile is whole.  The tile addresses are
