@@ -18,7 +18,12 @@
  *
  * Precision: bf16 inputs, fp32 scores / softmax state / accumulators, the
  * probabilities are rounded to bf16 (nearest-even) before the second
- * contraction, bf16 output (nearest-even).
+ * contraction and the row sum l is taken over the rounded values (O / l is
+ * then a convex combination of V rows whatever the rounding did; lse carries
+ * at most their 2^-8 relative error, i.e. 4e-3 absolute), bf16 output
+ * (nearest-even).  The softmax reference value of a row follows its running
+ * maximum lazily (it moves when exceeded by more than 8 in the base-2
+ * exponent); the quotient O / l does not depend on it.
  *
  * All functions are thread-compatible, not thread-safe: one context must not
  * be used from two host threads, or for two streams, at the same time.
@@ -81,7 +86,7 @@ int dit_attn_create(dit_attn_ctx** out_ctx, int device_id);
  *
  * The work is enqueued on `stream`; the call does not synchronise.  The first
  * call with a new (cu_seqlens, n_heads, head_dim) builds a work-list on the host
- * and uploads it (one device allocation and one stream-ordered copy); later
+ * and uploads it (one device allocation and one synchronous copy); later
  * calls with the same pack reuse it and do no host work beyond a compare.
  * The caller keeps ownership of every buffer.  Validation precedes any launch:
  * on a non-zero return `out` is untouched.

@@ -28,7 +28,7 @@ struct CachedPlan {
   int32_t head_dim = 0;
   dit::AttnKernel kernel = dit::AttnKernel::kIndependent128;
   int32_t n_splits = 1;  // key chunks per sequence (split-KV); part of the key
-  std::vector<dit::WorkItem> host_items;  // kept alive: source of the stream-ordered upload
+  std::vector<dit::WorkItem> host_items;
   dit::WorkItem* dev_items = nullptr;
   uint64_t last_use = 0;
 };
@@ -307,10 +307,11 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
     const size_t bytes = np->host_items.size() * sizeof(dit::WorkItem);
     e = hipMalloc(reinterpret_cast<void**>(&np->dev_items), bytes);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipMalloc(work-list)");
-    e = hipMemcpyAsync(np->dev_items, np->host_items.data(), bytes, hipMemcpyHostToDevice, s);
+    // Synchronous: the list may be read next by a launch on another stream than this call's.
+    e = hipMemcpy(np->dev_items, np->host_items.data(), bytes, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
       (void)hipFree(np->dev_items);
-      return fail_hip(ctx, e, "hipMemcpyAsync(work-list)");
+      return fail_hip(ctx, e, "hipMemcpy(work-list)");
     }
     if (ctx->plans.size() >= kMaxCachedPlans) {
       // Evict the least recently used plan.  hipFree waits for the device, so no kernel still reads it.

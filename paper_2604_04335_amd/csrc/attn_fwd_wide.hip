@@ -187,8 +187,8 @@ __device__ __forceinline__ void wide_stream(int (&va_)[T::NDB], int (&ka_)[T::NK
     constexpr int g = n / 8, h = (n % 8) / 4, kb = g / 2, i = 8 * (g % 2) + 2 * (n % 4);
     const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[h][kb][i], c, -mc[h]));
     const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[h][kb][i + 1], c, -mc[h]));
-    lsum[h] += p0 + p1;
     pb[h][kb][i >> 1] = pack_bf16x2(p0, p1);
+    lsum[h] = add_prob_pair(lsum[h], pb[h][kb][i >> 1]);
     asm volatile("" : "+v"(pb[h][kb][i >> 1]), "+v"(lsum[h]));
   };
   auto max_op = [&](auto kc) {
@@ -340,12 +340,12 @@ attn_fwd_wide_kernel(AttnParams p) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         mx[h] = max_with_other_half(mx[h]);
-        grow |= mx[h] > m_ref[h];
+        grow |= (mx[h] - m_ref[h]) * c > kRescaleLog2;
       }
       if (__builtin_amdgcn_ballot_w64(grow) != 0) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-          const float m_new = __builtin_fmaxf(m_ref[h], mx[h]);
+          const float m_new = (mx[h] - m_ref[h]) * c > kRescaleLog2 ? mx[h] : m_ref[h];
           const float alpha = __builtin_amdgcn_exp2f((m_ref[h] - m_new) * c);
           m_ref[h] = m_new;
           l_run[h] *= alpha;
@@ -424,8 +424,8 @@ attn_fwd_wide_kernel(AttnParams p) {
             const int key = 32 * kb + 8 * (i >> 2) + 4 * L.hh + (i & 3);
             if (key < rows.lo || key >= rows.hi) p0 = 0.f;
             if (key + 1 < rows.lo || key + 1 >= rows.hi) p1 = 0.f;
-            ls += p0 + p1;
             pb[h][kb][i >> 1] = pack_bf16x2(p0, p1);
+            ls = add_prob_pair(ls, pb[h][kb][i >> 1]);
             asm volatile("" : "+v"(pb[h][kb][i >> 1]), "+v"(ls));  // one pair at a time: keeps the register peak low
             SCHED_FENCE();
           }

@@ -20,7 +20,12 @@ sys.path.insert(0, os.path.dirname(__file__))
 from gpu_util import MAX_ABS_TOL, REL_L2_TOL, assert_parity, to_bits, to_dev, widen  # noqa: E402
 
 pytestmark = pytest.mark.gpu
-LSE_TOL = 1e-4
+# The row sum l is taken over the probabilities as rounded to bf16 for the second contraction (so that O / l is a convex
+# combination whatever the rounding did).  bf16 keeps 8 significant bits, so each term is off by at most 2^-8 relative
+# (half an ulp just above a power of two); all terms are positive, so l is off by at most 2^-8 relative and lse by at
+# most ln(1 + 2^-8) = 3.9e-3 (reached only by a row that one key dominates; typical rows average it down to < 1e-3).
+# The fp32 arithmetic around it adds ~1e-5.
+LSE_TOL = 4.0e-3
 
 
 @pytest.fixture(scope="module")
