@@ -312,6 +312,17 @@ __device__ __forceinline__ void mfma_stream(lds_char* smem, const int (&va)[T::N
   SCHED_FENCE();
 }
 
+// max(x[lane], x[lane ^ 32]) without going through LDS.  v_permlane32_swap exchanges the upper half of its first
+// register with the lower half of its second: starting from two copies of x, the first ends up with the lower
+// half-wave's values in all lanes and the second with the upper half-wave's.  Written as assembly: with the builtin
+// the compiler drops the second result when both inputs are the same value.  (The instruction needs two wait states
+// after a vector write of its operands.)
+__device__ __forceinline__ float max_with_other_half(float x) {
+  float lo = x, hi = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+  return __builtin_fmaxf(lo, hi);
+}
+
 // How far (in the base-2 exponent) a tile's row maximum may exceed the row's reference value before the reference moves.
 constexpr float kRescaleLog2 = 8.0f;
 
@@ -336,7 +347,7 @@ __device__ __forceinline__ void tile_softmax(f32x16 (&s)[T::NKB], int hh, TailRo
   for (int kb = 0; kb < T::NKB; ++kb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) mx = __builtin_fmaxf(mx, s[kb][i]);
-  mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
+  mx = max_with_other_half(mx);
 
   // The reference value m_ref of a row follows its running maximum lazily: it moves (and O^T and l are rescaled) only
   // when the tile's maximum exceeds it by more than kRescaleLog2 in the exponent, so probabilities lie in

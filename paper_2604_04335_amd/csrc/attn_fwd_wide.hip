@@ -49,17 +49,6 @@ struct Wide {
   static_assert(NF_QK % PD == 0 && NF_PV % PD == 0, "the ring position of a fragment must not depend on the step");
 };
 
-// max(x[lane], x[lane ^ 32]) without going through LDS.  v_permlane32_swap exchanges the upper half of its first
-// register with the lower half of its second: starting from two copies of x, the first ends up with the lower
-// half-wave's values in all lanes and the second with the upper half-wave's.  Written as assembly: with the builtin
-// the compiler drops the second result when both inputs are the same value.  (The instruction needs two wait states
-// after a vector write of its operands.)
-__device__ __forceinline__ float max_with_other_half(float x) {
-  float lo = x, hi = x;
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
-  return __builtin_fmaxf(lo, hi);
-}
-
 // Q fragments of one 32-row half (B operand of S^T = K Q^T; lane holds query row l32, d = 16*ks + 8*hh .. +7), loaded
 // straight into accumulation registers and awaited here.  (A value that the compiler classes as an ordinary register
 // and that an asm operand asks for in an accumulation register is copied in front of every use; these are defined in
