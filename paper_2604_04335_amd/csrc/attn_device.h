@@ -231,8 +231,11 @@ __device__ __forceinline__ void static_for(F&& f) {
 // An MFMA stream: optionally O^T += V^T P^T (V tile addressed by va), then steps [Q0, Q1) of S^T = K Q^T (K tile
 // addressed by ka; step q is k-step q / NKB of key block q % NKB, and step 0 of a block starts it from zero).
 // Operand reads run PD MFMAs ahead of their use, through a ring of PD operand registers.
+// va_ and ka_ pass through the empty asm statements below, so they are taken by reference and stay in their registers
+// (working on copies cost one move per address and tile).  Unrolling the tile loop over the buffer parity, with the
+// buffer as an immediate offset of the LDS instructions and no address arithmetic per tile at all, was 3 % slower.
 template <class T, bool DO_PV, int Q0, int Q1, int PD>
-__device__ __forceinline__ void mfma_stream(lds_char* smem, const int (&va)[T::NDB], const int (&ka)[T::NKS],
+__device__ __forceinline__ void mfma_stream(lds_char* smem, int (&va_)[T::NDB], int (&ka_)[T::NKS],
                                             const uint32_t (&pb)[T::NKB][8], const bf16x8 (&qf)[T::NKS],
                                             f32x16 (&o)[T::NDB], f32x16 (&s)[T::NKB]) {
   constexpr int NPV = DO_PV ? T::NPV : 0;
@@ -240,11 +243,6 @@ __device__ __forceinline__ void mfma_stream(lds_char* smem, const int (&va)[T::N
   constexpr int N = NPV + NQK;
   static_assert(Q0 >= 0 && Q0 <= Q1 && Q1 <= T::NQK, "QK step range");
   bf16x8 frag[PD];
-  int va_[T::NDB], ka_[T::NKS];
-#pragma unroll
-  for (int i = 0; i < T::NDB; ++i) va_[i] = va[i];
-#pragma unroll
-  for (int i = 0; i < T::NKS; ++i) ka_[i] = ka[i];
 
   auto load_step = [&](auto jc) {
     constexpr int J = decltype(jc)::value;
