@@ -177,8 +177,7 @@ __device__ __forceinline__ void wide_stream(int (&va_)[T::NDB], int (&ka_)[T::NK
     const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[h][kb][i], c, -mc[h]));
     const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[h][kb][i + 1], c, -mc[h]));
     pb[h][kb][i >> 1] = pack_bf16x2(p0, p1);
-    lsum[h] = add_prob_pair(lsum[h], pb[h][kb][i >> 1]);
-    asm volatile("" : "+v"(pb[h][kb][i >> 1]), "+v"(lsum[h]));
+    asm volatile("" : "+v"(pb[h][kb][i >> 1]));
   };
   auto max_op = [&](auto kc) {
     constexpr int k = decltype(kc)::value;
@@ -390,8 +389,16 @@ attn_fwd_wide_kernel(AttnParams p) {
         }
       };
       wide_stream<T, true, true, true, true, true>(va, ka, k_step(), ring, qf, o, cur, nxt, pb, mc, c, lsum, mx, issue);
-      l_run[0] += lsum[0];
-      l_run[1] += lsum[1];
+      // Row sums over the packed probabilities, in one burst after the last MFMA has been issued: the dot products share
+      // a pipe with the MFMAs, and one between two MFMAs holds both up.
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int kb = 0; kb < T::NKB; ++kb)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) lsum[h] = add_prob_pair(lsum[h], pb[h][kb][i]);
+        l_run[h] += lsum[h];
+      }
       next_k();
       next_v();
       finish_max();
