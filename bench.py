@@ -30,9 +30,9 @@ DEFAULT_WORKLOAD = "mixed_varlen"
 # each scaled by what the same counter reads for the 1 GiB copy of --copy-calibration; the summaries and the
 # commands are under profiles/.  None where no such run has been made for the workload.
 MEASURED_HBM_BYTES = {
-    "mixed_varlen": 2_634_149_478,  # fetch 1135053.6 KiB x 2.000 + write 302304.4 KiB x 1.000
-    "sp_shard": 4_475_975_782,      # fetch 2088799.6 KiB x 2.000 + write 193470.9 KiB x 1.000
-    "t2v_single": 1_406_442_701,    # fetch 621769.5 KiB x 2.000 + write 129940.2 KiB x 1.000
+    "mixed_varlen": 2_569_645_363,  # fetch 1103933.2 KiB x 2.000 + write 301552.9 KiB x 1.000
+    "sp_shard": 4_484_600_320,      # fetch 2093346.6 KiB x 2.000 + write 192799.3 KiB x 1.000
+    "t2v_single": 1_435_310_797,    # fetch 635891.0 KiB x 2.000 + write 129888.7 KiB x 1.000
 }
 
 
