@@ -317,8 +317,8 @@ __device__ __forceinline__ void mfma_stream(lds_char* smem, int (&va_)[T::NDB], 
 // after a vector write of its operands.)
 __device__ __forceinline__ float max_with_other_half(float x) {
   float lo = x, hi = x;
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
-  return __builtin_fmaxf(lo, hi);
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\tv_max_f32 %0, %0, %1" : "+v"(lo), "+v"(hi));
+  return lo;
 }
 
 // How far (in the base-2 exponent) a tile's row maximum may exceed the row's reference value before the reference moves.
@@ -340,11 +340,27 @@ __device__ __forceinline__ void tile_softmax(f32x16 (&s)[T::NKB], int hh, TailRo
       }
   }
 
-  float mx = s[0][0];
+  // v_max3_f32 written out, one asm statement per block of 16 scores: through fmaxf the compiler first "quiets"
+  // every operand it cannot prove canonical with a v_max_f32 x, x, x (MFMA results, asm results), six more
+  // instructions per tile; and it pads every asm statement with an s_nop.
+  float mx;
+#define DIT_S(k, i) "v"(s[k][i])
+  asm("v_max3_f32 %0, %1, %2, %3\n\tv_max3_f32 %0, %0, %4, %5\n\tv_max3_f32 %0, %0, %6, %7\n\t"
+      "v_max3_f32 %0, %0, %8, %9\n\tv_max3_f32 %0, %0, %10, %11\n\tv_max3_f32 %0, %0, %12, %13\n\t"
+      "v_max3_f32 %0, %0, %14, %15\n\tv_max_f32 %0, %0, %16"
+      : "=&v"(mx)
+      : DIT_S(0, 0), DIT_S(0, 1), DIT_S(0, 2), DIT_S(0, 3), DIT_S(0, 4), DIT_S(0, 5), DIT_S(0, 6), DIT_S(0, 7), DIT_S(0, 8),
+        DIT_S(0, 9), DIT_S(0, 10), DIT_S(0, 11), DIT_S(0, 12), DIT_S(0, 13), DIT_S(0, 14), DIT_S(0, 15));
 #pragma unroll
-  for (int kb = 0; kb < T::NKB; ++kb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) mx = __builtin_fmaxf(mx, s[kb][i]);
+  for (int kb = 1; kb < T::NKB; ++kb)
+    asm("v_max3_f32 %0, %0, %1, %2\n\tv_max3_f32 %0, %0, %3, %4\n\tv_max3_f32 %0, %0, %5, %6\n\t"
+        "v_max3_f32 %0, %0, %7, %8\n\tv_max3_f32 %0, %0, %9, %10\n\tv_max3_f32 %0, %0, %11, %12\n\t"
+        "v_max3_f32 %0, %0, %13, %14\n\tv_max3_f32 %0, %0, %15, %16"
+        : "+v"(mx)
+        : DIT_S(kb, 0), DIT_S(kb, 1), DIT_S(kb, 2), DIT_S(kb, 3), DIT_S(kb, 4), DIT_S(kb, 5), DIT_S(kb, 6), DIT_S(kb, 7),
+          DIT_S(kb, 8), DIT_S(kb, 9), DIT_S(kb, 10), DIT_S(kb, 11), DIT_S(kb, 12), DIT_S(kb, 13), DIT_S(kb, 14),
+          DIT_S(kb, 15));
+#undef DIT_S
   mx = max_with_other_half(mx);
 
   // The reference value m_ref of a row follows its running maximum lazily: it moves (and O^T and l are rescaled) only
