@@ -151,8 +151,9 @@ def test_both_kernels_give_the_same_bits(runner):
 @pytest.mark.parametrize("head_dim", [64, 128])
 def test_wide_kernel_gives_the_same_bits(runner, head_dim):
     """The 64-rows-per-wavefront kernel against the ping-pong kernel on the same 256-row work-list: ragged tiles, a
-    one-tile and a two-tile sequence, an odd and an even number of tiles; and against the oracle."""
-    w = make_custom([1500, 64, 128, 1, 333, 2049], 3, head_dim, seed=31)
+    one-tile and a two-tile sequence, lengths around the tile and item sizes, an empty sequence, an odd and an even
+    number of tiles; and against the oracle."""
+    w = make_custom([1500, 64, 128, 1, 333, 2049, 63, 65, 0, 127, 129, 255, 257, 2], 3, head_dim, seed=31)
     a = runner.run(w, kernel=da.KERNEL_PINGPONG)
     b = runner.run(w, kernel=da.KERNEL_WIDE)
     assert np.array_equal(a, b)
