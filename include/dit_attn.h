@@ -170,10 +170,10 @@ int dit_attn_sp_unpack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int6
  * image steps are short, video steps long):
  *     DIT_ATTN_KERNEL_AUTO   (-1) chosen per pack: packs with at least one
  *                                 256-row tile per compute unit run a 256-row
- *                                 kernel (the wide one if head_dim is 128 and
- *                                 an item has at most 48 key tiles on
- *                                 average, else the ping-pong one), smaller
- *                                 packs the 128-row kernel
+ *                                 kernel (the wide one if an item has at
+ *                                 most 48 key tiles on average, 200 at
+ *                                 head_dim 64; else the ping-pong one),
+ *                                 smaller packs the 128-row kernel
  *     DIT_ATTN_KERNEL_128     (0) 128 query rows per tile
  *     DIT_ATTN_KERNEL_PINGPONG(1) 256 rows per tile, two alternating groups
  *     DIT_ATTN_KERNEL_WIDE    (2) 256 rows per tile, 64 per wavefront

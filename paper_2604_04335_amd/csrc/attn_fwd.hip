@@ -233,7 +233,8 @@ AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_
   // The 256-row kernels need at least one item per compute unit; smaller packs run the 128-row kernel, which cuts
   // them into twice as many items.  Among the 256-row kernels the wide one is ahead for short key sequences (its
   // items start and end without an idle phase, and it keeps a higher clock): measured at head dimension 128 with
-  // N(0,1) data, +6 % at 16-20 key tiles per item, +1 % at 48, -2 % at 68, -5 % from 128 tiles on.
+  // N(0,1) data, +6 % at 16-20 key tiles per item, +1 % at 48, -2 % at 68, -5 % from 128 tiles on; at head dimension
+  // 64, +10 % up to 68 tiles and level at 321.
   const int32_t* ck = cu_seqlens_k ? cu_seqlens_k : cu_seqlens;
   int64_t items256 = 0, tiles = 0;
   for (int32_t i = 0; i < n_seqs; ++i) {
@@ -244,7 +245,7 @@ AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_
     tiles += it * ((lk + 63) / 64);
   }
   if (items256 < n_cus) return AttnKernel::kIndependent128;
-  return head_dim == 128 && tiles <= 48 * items256 ? AttnKernel::kWide256 : AttnKernel::kPingPong256;
+  return tiles <= (head_dim == 128 ? 48 : 200) * items256 ? AttnKernel::kWide256 : AttnKernel::kPingPong256;
 }
 
 hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim, int grid, hipStream_t stream) {
