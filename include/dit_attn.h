@@ -170,10 +170,8 @@ int dit_attn_sp_unpack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int6
  * image steps are short, video steps long):
  *     DIT_ATTN_KERNEL_AUTO   (-1) chosen per pack: packs with at least one
  *                                 256-row tile per compute unit run a 256-row
- *                                 kernel (the wide one if an item has at
- *                                 most 48 key tiles on average, 200 at
- *                                 head_dim 64; else the ping-pong one),
- *                                 smaller packs the 128-row kernel
+ *                                 kernel (the ping-pong one), smaller
+ *                                 packs the 128-row kernel
  *     DIT_ATTN_KERNEL_128     (0) 128 query rows per tile
  *     DIT_ATTN_KERNEL_PINGPONG(1) 256 rows per tile, two alternating groups
  *     DIT_ATTN_KERNEL_WIDE    (2) 256 rows per tile, 64 per wavefront
@@ -211,6 +209,16 @@ int dit_attn_set_split_kv(dit_attn_ctx* ctx, int max_splits);
  * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL or DIT_ATTN_ERR_HIP.
  */
 int dit_attn_last_launch_clock(dit_attn_ctx* ctx, double* shader_mhz, double* kernel_ms);
+
+/*
+ * Which attention kernel the last forward call on `ctx` launched: one of
+ * DIT_ATTN_KERNEL_128 / _PINGPONG / _WIDE (the kernel that ran: a negative
+ * scale turns a wide-kernel pack into a ping-pong launch), or
+ * DIT_ATTN_KERNEL_AUTO (-1) if no attention kernel has been launched yet.
+ * For measurements that name the kernel they timed.  Host state only; NULL
+ * returns DIT_ATTN_KERNEL_AUTO.
+ */
+int dit_attn_last_launch_kernel(const dit_attn_ctx* ctx);
 
 /*
  * Text of the last error recorded in `ctx` (or of the last failed

@@ -37,6 +37,7 @@ __all__ = [
     "dit_attn_set_kernel",
     "dit_attn_set_split_kv",
     "dit_attn_last_launch_clock",
+    "dit_attn_last_launch_kernel",
     "KERNEL_AUTO",
     "KERNEL_128",
     "KERNEL_PINGPONG",
@@ -118,6 +119,8 @@ def load_library() -> ctypes.CDLL:
     lib.dit_attn_set_split_kv.argtypes = [vp, ctypes.c_int]
     lib.dit_attn_set_kernel.restype = ctypes.c_int
     lib.dit_attn_set_kernel.argtypes = [vp, ctypes.c_int]
+    lib.dit_attn_last_launch_kernel.restype = ctypes.c_int
+    lib.dit_attn_last_launch_kernel.argtypes = [vp]
     lib.dit_attn_last_launch_clock.restype = ctypes.c_int
     lib.dit_attn_last_launch_clock.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.dit_attn_plan.restype = i64
@@ -184,6 +187,11 @@ def dit_attn_last_launch_clock(ctx):
     if rc != 0:
         raise DitAttnError(rc, dit_attn_last_error(ctx))
     return mhz.value, ms.value
+
+
+def dit_attn_last_launch_kernel(ctx) -> int:
+    """KERNEL_128 / KERNEL_PINGPONG / KERNEL_WIDE: the kernel the last forward call launched; KERNEL_AUTO before any."""
+    return int(load_library().dit_attn_last_launch_kernel(ctypes.c_void_p(ctx)))
 
 
 def dit_attn_destroy(ctx) -> None:

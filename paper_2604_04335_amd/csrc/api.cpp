@@ -47,6 +47,7 @@ struct dit_attn_ctx {
   uint32_t* sync = nullptr;     // device, 8 words: work counters (zero between launches) and the last launch's clock sample
   uint64_t tick = 0;
   int force_kernel = -1;        // -1: chosen per pack; else a dit::AttnKernel value (dit_attn_set_kernel)
+  int last_kernel = -1;         // kernel of the last attention launch (dit_attn_last_launch_kernel)
   int max_splits = 1;           // split-KV: at most this many key chunks per sequence (dit_attn_set_split_kv); 1 = off
   float* workspace = nullptr;   // split-KV partial results and their lse
   size_t workspace_bytes = 0;
@@ -202,6 +203,8 @@ int dit_attn_last_launch_clock(dit_attn_ctx* ctx, double* shader_mhz, double* ke
   return DIT_ATTN_OK;
 }
 
+int dit_attn_last_launch_kernel(const dit_attn_ctx* ctx) { return ctx ? ctx->last_kernel : -1; }
+
 const char* dit_attn_last_error(const dit_attn_ctx* ctx) {
   return ctx ? ctx->error.c_str() : g_create_error.c_str();
 }
@@ -212,7 +215,7 @@ int64_t dit_attn_plan(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads
   const int rc = check_shape_args(cu_seqlens, n_seqs, n_heads, head_dim, msg);
   if (rc != DIT_ATTN_OK) return rc;
   if (capacity_items > 0 && !items) return DIT_ATTN_ERR_NULL;
-  const dit::AttnKernel kernel = dit::attn_fwd_select(cu_seqlens, nullptr, n_seqs, n_heads, head_dim, kMi355xComputeUnits);
+  const dit::AttnKernel kernel = dit::attn_fwd_select(cu_seqlens, n_seqs, n_heads, kMi355xComputeUnits);
   const int bm = dit::attn_fwd_block_m(kernel);
   if (block_m) *block_m = bm;
   std::vector<dit::WorkItem> list;
@@ -261,7 +264,7 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
   CachedPlan* plan = nullptr;
   const size_t cu_n = static_cast<size_t>(n_seqs) + 1;
   const dit::AttnKernel kernel = ctx->force_kernel >= 0 ? static_cast<dit::AttnKernel>(ctx->force_kernel)
-                                                        : dit::attn_fwd_select(cu_seqlens, cu_k, n_seqs, n_heads, head_dim, ctx->n_cus);
+                                                        : dit::attn_fwd_select(cu_seqlens, n_seqs, n_heads, ctx->n_cus);
   // Split-KV (opt-in): a pack of the 128-row kernel with fewer items than compute units cuts every sequence's keys into
   // chunks of at least four key tiles, as many as it takes to reach two items per compute unit, and merges the parts.
   int32_t n_splits = 1;
@@ -377,6 +380,8 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
   p.negate = scale < 0.f ? 1 : 0;
   e = dit::attn_fwd_launch(p, plan->kernel, head_dim, grid, s);
   if (e != hipSuccess) return fail_hip(ctx, e, "kernel launch");
+  ctx->last_kernel = plan->kernel == dit::AttnKernel::kWide256 && p.negate ? static_cast<int>(dit::AttnKernel::kPingPong256)
+                                                                           : static_cast<int>(plan->kernel);
   if (n_splits > 1) {
     dit::MergeParams m{};
     for (int32_t i = 0; i < n_splits; ++i) {

@@ -228,24 +228,14 @@ static hipError_t launch_t(const AttnParams& p, int grid, hipStream_t stream) {
 int attn_fwd_block_m(AttnKernel kernel) { return kernel == AttnKernel::kIndependent128 ? 128 : 256; }
 int attn_fwd_wgs_per_cu(AttnKernel kernel) { return kernel == AttnKernel::kIndependent128 ? 2 : 1; }
 
-AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_k, int32_t n_seqs, int32_t n_heads,
-                           int32_t head_dim, int n_cus) {
+AttnKernel attn_fwd_select(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int n_cus) {
   // The 256-row kernels need at least one item per compute unit; smaller packs run the 128-row kernel, which cuts
-  // them into twice as many items.  Among the 256-row kernels the wide one is ahead for short key sequences (its
-  // items start and end without an idle phase, and it keeps a higher clock): measured at head dimension 128 with
-  // N(0,1) data, +6 % at 16-20 key tiles per item, +1 % at 48, -2 % at 68, -5 % from 128 tiles on; at head dimension
-  // 64, +10 % up to 68 tiles and level at 321.
-  const int32_t* ck = cu_seqlens_k ? cu_seqlens_k : cu_seqlens;
-  int64_t items256 = 0, tiles = 0;
-  for (int32_t i = 0; i < n_seqs; ++i) {
-    const int64_t lq = cu_seqlens[i + 1] - cu_seqlens[i], lk = ck[i + 1] - ck[i];
-    if (lq == 0 || lk == 0) continue;
-    const int64_t it = (lq + 255) / 256 * n_heads;
-    items256 += it;
-    tiles += it * ((lk + 63) / 64);
-  }
-  if (items256 < n_cus) return AttnKernel::kIndependent128;
-  return tiles <= (head_dim == 128 ? 48 : 200) * items256 ? AttnKernel::kWide256 : AttnKernel::kPingPong256;
+  // them into twice as many items.  Of the 256-row kernels the ping-pong one is ahead at every sequence length once
+  // the chip has warmed up (6-10 % at head dimension 128, 0-4 % at 64); measured on a cold chip, in the first ~20 ms
+  // after idle, whichever kernel runs second looks faster.
+  int64_t items256 = 0;
+  for (int32_t i = 0; i < n_seqs; ++i) items256 += (int64_t)((cu_seqlens[i + 1] - cu_seqlens[i] + 255) / 256) * n_heads;
+  return items256 >= n_cus ? AttnKernel::kPingPong256 : AttnKernel::kIndependent128;
 }
 
 hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim, int grid, hipStream_t stream) {

@@ -169,6 +169,12 @@ def test_launch_clock_sample(runner):
     mhz, ms = da.dit_attn_last_launch_clock(runner.ctx)
     assert 300.0 < mhz < 2600.0, mhz
     assert 0.0 < ms < 1000.0, ms
+    # 8 x 8 = 64 items of 256 rows: fewer than compute units, so the 128-row kernel ran; a forced kernel is reported too
+    assert da.dit_attn_last_launch_kernel(runner.ctx) == da.KERNEL_128
+    runner.run(w, kernel=da.KERNEL_WIDE)
+    assert da.dit_attn_last_launch_kernel(runner.ctx) == da.KERNEL_WIDE
+    runner.run(w, scale=-0.5, kernel=da.KERNEL_WIDE)
+    assert da.dit_attn_last_launch_kernel(runner.ctx) == da.KERNEL_PINGPONG
 
 
 def test_head_subset_equals_heads_of_wider_run(runner):
