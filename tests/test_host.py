@@ -107,3 +107,13 @@ def test_plan_rejects_bad_arguments():
     buf = np.zeros(4, dtype=np.int32)
     arr = np.array([0, 1000], dtype=np.int32)
     assert lib.dit_attn_plan(arr.ctypes.data_as(i32p), 1, 2, 128, buf.ctypes.data_as(i32p), 1, None) == -8
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: `bench.py --gpus N` with N > 1 exits with a message and a non-zero status, before touching a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
