@@ -270,6 +270,37 @@ def test_non_default_stream(runner):
     assert_parity(to_bits(out), ref, "stream")
 
 
+@pytest.mark.parametrize("lens,heads", [([300, 70], 3), ([4096], 16)], ids=["128-row kernel", "ping-pong kernel"])
+def test_graph_capture_and_replay(runner, lens, heads):
+    """A forward call captured into a HIP graph (after one eager call has cached the pack's work-list: the first call
+    allocates and copies, which a capture cannot record) and replayed several times, with eager work and
+    synchronisations between the replays: every replay reproduces the eager bits.  The work counters that the kernel
+    uses are cleared by its last workgroup, not by the host, so a replay finds them as a launch leaves them."""
+    w = make_custom(lens, heads, 128, seed=35)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    eager = torch.empty_like(q)
+    da.dit_attn_varlen_fwd(runner.ctx, q, k, v, w.cu_seqlens, heads, 128, w.scale, eager, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    out = torch.zeros_like(q)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        da.dit_attn_varlen_fwd(runner.ctx, q, k, v, w.cu_seqlens, heads, 128, w.scale, out, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for i in range(4):
+        out.zero_()
+        # the program's own eager work between replays: another pack through the same context, and a reduction
+        other = runner.run(make_custom([200 + 17 * i], 2, 128, seed=36 + i))
+        assert other.shape[0] == 200 + 17 * i
+        _ = float(q.float().sum().item())
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {i}"
+    rows = sample_rows(w.cu_seqlens, seed=5, block=16, max_rows=64)
+    ref = orc.attention_varlen_rows(w.q, w.k, w.v, w.cu_seqlens, w.scale, rows)
+    assert_parity(to_bits(out)[rows], ref, "graph replay")
+
+
 def test_empty_inputs_launch_nothing(runner):
     da.dit_attn_varlen_fwd(runner.ctx, 0, 0, 0, np.array([0], dtype=np.int32), 2, 128, 1.0, 0, None)
     da.dit_attn_varlen_fwd(runner.ctx, 0, 0, 0, np.array([0, 0, 0], dtype=np.int32), 2, 128, 1.0, 0, None)
