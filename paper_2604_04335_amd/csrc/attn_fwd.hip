@@ -58,25 +58,27 @@ attn_fwd_kernel(AttnParams p) {
     L.operand_addrs((uint32_t)(uintptr_t)smem, (uint32_t)(uintptr_t)smem, ka, va);
 
     if (nt == 1 && tid == 0) s_item[par] = take_item(p);  // visible after the barrier below
-    for (int t = 0; t < nt; ++t) {
+    for (int t = 0; t + 1 < nt; ++t) {
       // Tile t has landed (this wave's loads), and after the barrier everyone's; everyone is also done
       // reading the other buffers (tile t-1), so they can be refilled with tile t+1 while tile t is used.
       wait_loads();
       wg_barrier();
       if (t + 2 == nt && tid == 0) s_item[par] = take_item(p);  // visible after the barrier of the last tile
-      if (t + 1 < nt) load_tile(t + 1);
+      load_tile(t + 1);
       mfma_stream<T, false, 0, T::NQK, kPrefetch>(smem, va, ka, pb, qf, o, s);
-      if (t + 1 < nt) {
-        tile_softmax<T, false>(s, L.hh, TailRows{0, T::BN}, c, pb, o, m_ref, l_run);
-      } else {
-        tile_softmax<T, true>(s, L.hh, tail_rows<T>(kv_len), c, pb, o, m_ref, l_run);
-      }
+      tile_softmax<T, false>(s, L.hh, TailRows{0, T::BN}, c, pb, o, m_ref, l_run);
       mfma_stream<T, true, 0, 0, kPrefetch>(smem, va, ka, pb, qf, o, s);
 #pragma unroll
       for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
 #pragma unroll
       for (int db = 0; db < T::NDB; ++db) va[db] ^= T::TILE_B;
     }
+    // The last tile (masked), outside the loop: one copy of each softmax variant, no test per tile.
+    wait_loads();
+    wg_barrier();
+    mfma_stream<T, false, 0, T::NQK, kPrefetch>(smem, va, ka, pb, qf, o, s);
+    tile_softmax<T, true>(s, L.hh, tail_rows<T>(kv_len), c, pb, o, m_ref, l_run);
+    mfma_stream<T, true, 0, 0, kPrefetch>(smem, va, ka, pb, qf, o, s);
 
     store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run, m_ref);
     wg_barrier();  // the next item's first loads overwrite the buffers of parity 0
