@@ -168,10 +168,11 @@ int dit_attn_sp_unpack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int6
  * Kernel choice of a context.  The library has three kernels for the same
  * operation (which one is fastest depends on the pack, Section 4.3 / Table 3:
  * image steps are short, video steps long):
- *     DIT_ATTN_KERNEL_AUTO   (-1) chosen per pack: packs with at least one
- *                                 256-row tile per compute unit run a 256-row
- *                                 kernel (the ping-pong one), smaller
- *                                 packs the 128-row kernel
+ *     DIT_ATTN_KERNEL_AUTO   (-1) chosen per pack: the ping-pong kernel when
+ *                                 its 256-row items fill the compute units,
+ *                                 the 128-row kernel for packs with well
+ *                                 under one such item per compute unit or
+ *                                 whose last round would be under half full
  *     DIT_ATTN_KERNEL_128     (0) 128 query rows per tile
  *     DIT_ATTN_KERNEL_PINGPONG(1) 256 rows per tile, two alternating groups
  *     DIT_ATTN_KERNEL_WIDE    (2) 256 rows per tile, 64 per wavefront

@@ -133,15 +133,17 @@ def test_pack_isolation_bitwise(runner):
 
 
 def test_both_kernels_give_the_same_bits(runner):
-    """A large pack runs the 256-row ping-pong kernel, a small one the 128-row kernel: same bits per sequence."""
-    w = make_custom([8192, 300, 77], 8, 64, seed=28)
-    items, bm = da.dit_attn_plan(w.cu_seqlens, 8, 64)
+    """A large pack runs the 256-row ping-pong kernel, a small one the 128-row kernel: same bits per sequence.
+    (35 query tiles x 12 heads = 420 items of 256 rows: 1.64 per compute unit, so the ping-pong kernel is chosen.)"""
+    w = make_custom([8192, 300, 77], 12, 64, seed=28)
+    items, bm = da.dit_attn_plan(w.cu_seqlens, 12, 64)
     assert bm == 256
     full = runner.run(w)
+    assert da.dit_attn_last_launch_kernel(runner.ctx) == da.KERNEL_PINGPONG
     for s, e in ((8192, 8492), (8492, 8569)):
-        alone = make_custom([e - s], 8, 64, seed=0)
+        alone = make_custom([e - s], 12, 64, seed=0)
         alone.q, alone.k, alone.v = w.q[s:e].copy(), w.k[s:e].copy(), w.v[s:e].copy()
-        assert da.dit_attn_plan(alone.cu_seqlens, 8, 64)[1] == 128
+        assert da.dit_attn_plan(alone.cu_seqlens, 12, 64)[1] == 128
         assert np.array_equal(runner.run(alone), full[s:e])
     rows = sample_rows(w.cu_seqlens, seed=3, block=256)
     ref = orc.attention_varlen_rows(w.q, w.k, w.v, w.cu_seqlens, w.scale, rows)
