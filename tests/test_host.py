@@ -117,3 +117,19 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in (r.stdout + r.stderr)
+
+
+def test_kernel_choice_by_items_per_compute_unit():
+    """dit_attn_plan's block_m shows which kernel family a pack gets on a 256-CU device: the 128-row kernel for well
+    under one 256-row item per compute unit and for packs of at most three rounds whose last round would be under half
+    full, the 256-row (ping-pong) kernel otherwise.  4096 tokens are 16 items of 256 rows per head."""
+    def block_m(lens, heads):
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        return da.dit_attn_plan(cu, heads, 128)[1]
+    expect = {8: 128, 9: 128, 10: 256, 12: 256, 16: 256, 17: 128, 20: 128, 24: 128, 25: 256, 32: 256, 40: 128, 41: 256,
+              48: 256, 49: 256, 64: 256}
+    for heads, bm in expect.items():
+        assert block_m([4096], heads) == bm, heads
+    assert block_m([20506], 24) == 256
+    assert block_m([4352] * 4, 24) == 256
+    assert block_m([1024], 8) == 128
