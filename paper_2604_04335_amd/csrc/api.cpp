@@ -277,10 +277,15 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
       items += (lq + 127) / 128 * n_heads;
       min_tiles = std::min<int64_t>(min_tiles, (lk + 63) / 64);
     }
-    // Measured on MI355X: the two extra launches (fill, merge) cost about as much as is gained below ~3000 keys.
-    if (items > 0 && items < ctx->n_cus && min_tiles >= 48) {
+    if (items > 0 && items < ctx->n_cus) {
       const int64_t want = (2 * static_cast<int64_t>(ctx->n_cus) + items - 1) / items;
-      n_splits = static_cast<int32_t>(std::max<int64_t>(1, std::min<int64_t>({want, ctx->max_splits, min_tiles / 4})));
+      const int64_t n = std::max<int64_t>(1, std::min<int64_t>({want, ctx->max_splits, min_tiles / 4}));
+      // Measured on MI355X (128-row kernel, one workgroup per compute unit, head dimension 128): an unsplit call takes
+      // about 10 us + 1.1 us per key tile, a call split n ways 37 us (fill and merge launches, fp32 partials, one more
+      // start-up per chunk) + 1.7 / n of the unsplit time.  Split only where that is a gain: from 49 key tiles on for
+      // n = 4, 68 for n = 3, 34 for n = 8.
+      const double t_unsplit = 10.0 + 1.1 * static_cast<double>(min_tiles);
+      if (n > 1 && t_unsplit * (1.0 - 1.7 / static_cast<double>(n)) > 37.0) n_splits = static_cast<int32_t>(n);
     }
   }
   for (auto& p : ctx->plans) {

@@ -221,9 +221,9 @@ def test_new_entry_points_reject_bad_arguments(ctx):
 
 @pytest.mark.parametrize("lens,H,D,max_splits", [
     ([4096], 4, 64, 8),             # 128 items of 128 rows -> 4 chunks of 1024 keys
-    ([3100, 3073, 5000], 2, 128, 8),  # ragged: chunks of whole tiles, short last chunks, sequences with different chunk counts
+    ([6200, 6147, 10000], 1, 128, 8),  # ragged: chunks of whole tiles, short last chunks, sequences with different chunk counts
     ([6145], 1, 128, 3),
-    ([3500], 3, 64, 2),
+    ([16000], 1, 64, 2),            # two chunks pay only for long sequences
 ])
 def test_split_kv_matches_oracle_and_unsplit_result(ctx, lens, H, D, max_splits):
     w = make_custom(lens, H, D, seed=48)
@@ -277,7 +277,7 @@ def test_split_kv_leaves_large_packs_alone_and_rejects_bad_counts(ctx):
 
 
 def test_split_kv_cross_attention(ctx):
-    w = make_cross([600, 100], [5000, 3072], 2, 128, seed=50)
+    w = make_cross([600, 100], [5000, 3300], 2, 128, seed=50)
     q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
     out = torch.empty_like(q)
     da.dit_attn_set_split_kv(ctx, 4)
