@@ -190,8 +190,9 @@ int dit_attn_set_kernel(dit_attn_ctx* ctx, int kernel);
 /*
  * Split-KV for small packs (paper Section 3 / Table 3: a low-resolution image step is far too small to fill a GPU).
  * With max_splits > 1, a pack that runs the 128-row kernel and has fewer work items than compute units has the keys of
- * every sequence cut into up to max_splits chunks (only if every sequence has at least 3072 keys; as many chunks as it
- * takes to reach two items per compute unit); the chunks run as separate items that leave normalised fp32 partial results and their
+ * every sequence cut into up to max_splits chunks (as many as it takes to reach two items per compute unit, and only
+ * where a cost model measured on MI355X says the split pays: roughly from 3100 keys on for four chunks, 2200 for eight,
+ * 4400 for three, 13800 for two); the chunks run as separate items that leave normalised fp32 partial results and their
  * log-sum-exp in a workspace owned by the context (grown with hipMalloc when a call needs more), and one merge kernel
  * on the same stream writes `out`.  Off (max_splits = 1) by default, because it changes the summation order: with it
  * a sequence's bits depend on what it is packed with (they stay within the same tolerance of the exact result).
