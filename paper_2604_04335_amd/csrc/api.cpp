@@ -363,9 +363,21 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
   }
   float* part_out = n_splits > 1 ? ctx->workspace : nullptr;
   float* part_lse = n_splits > 1 ? ctx->workspace + static_cast<size_t>(n_splits) * total_q * n_heads * head_dim : nullptr;
-  if (n_splits > 1) {  // a sequence with fewer chunks than n_splits leaves parts unwritten: their weight must be 0
-    e = dit::fill_neg_inf_launch(part_lse, static_cast<int64_t>(n_splits) * total_q * n_heads, s);
-    if (e != hipSuccess) return fail_hip(ctx, e, "fill kernel launch");
+  if (n_splits > 1) {
+    // A sequence with fewer chunks than n_splits (or without keys) leaves parts unwritten: their weight must be 0.
+    // Packs whose sequences all fill every part (the common single-shape pack) skip that launch.
+    bool complete = true;
+    const int32_t* ck = cu_k ? cu_k : cu_seqlens;
+    for (int32_t i = 0; i < n_seqs && complete; ++i) {
+      const int64_t lq = cu_seqlens[i + 1] - cu_seqlens[i], lk = ck[i + 1] - ck[i];
+      if (lq == 0) continue;
+      const int64_t tiles = (lk + 63) / 64, per_part = (tiles + n_splits - 1) / n_splits;
+      complete = lk > 0 && (tiles + per_part - 1) / per_part == n_splits;
+    }
+    if (!complete) {
+      e = dit::fill_neg_inf_launch(part_lse, static_cast<int64_t>(n_splits) * total_q * n_heads, s);
+      if (e != hipSuccess) return fail_hip(ctx, e, "fill kernel launch");
+    }
   }
 
   dit::AttnParams p;
