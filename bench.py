@@ -54,9 +54,11 @@ def _prewarm(torch, step):
         torch.cuda.synchronize()
 
 
-def time_workload(da, torch, ctx, w, steps: int, warmup: int):
+def time_workload(da, torch, ctx, w, steps: int, warmup: int, zero_operands: bool = False):
     """Returns (wall ms per step, mean kernel ms from per-step event pairs, list of per-step ms, out tensor)."""
     q, k, v = _to_dev(w.q, torch), _to_dev(w.k, torch), _to_dev(w.v, torch)
+    if zero_operands:  # same launch, same instruction stream; only the switching activity of the operands differs
+        q, k, v = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
     out = torch.empty_like(q)
     stream = torch.cuda.current_stream().cuda_stream
     H, D = w.n_heads, w.head_dim
@@ -246,6 +248,8 @@ def main():
     ap.add_argument("--op", default="attn", choices=["attn", "merge", "cross", "layout", "sched"],
                     help="attn: the denoising-step self-attention (the headline line); merge / cross: one line for the "
                          "partial-result merge kernel (HBM bound) or for cross-attention against text keys")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="power check, not the metric: time the same launch on all-zero Q, K, V (the line says so in `data`)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device-to-device copy (a kernel of known HBM traffic, for counter scaling)")
     args = ap.parse_args()
@@ -283,7 +287,7 @@ def main():
 
     w = make_workload(args.workload, args.seed)
     flops = attention_flops(w.cu_seqlens, w.n_heads, w.head_dim)
-    wall_ms, kern_ms, per, _ = time_workload(da, torch, ctx, w, args.steps, args.warmup)
+    wall_ms, kern_ms, per, _ = time_workload(da, torch, ctx, w, args.steps, args.warmup, args.zero_operands)
     tflops = flops / (wall_ms * 1e-3) / 1e12
     kern_tflops = flops / (kern_ms * 1e-3) / 1e12
 
@@ -307,7 +311,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
-        "data": "synthetic",
+        "data": "all-zero operands (power check, not the metric)" if args.zero_operands else "synthetic",
         "config": {
             "workload": w.name,
             "seq_lens": w.seq_lens,
