@@ -238,6 +238,27 @@ def test_increasing_logits_force_rescaling(runner):
     assert_parity(got, ref, "increasing logits")
 
 
+def test_lazy_reference_staircase(runner):
+    """Logits that are constant per 64-key tile and step from tile to tile by just under the rescale threshold (2^8 in
+    the base-2 exponent: the reference stays), just over it (it moves), by a huge amount, and down again; every
+    kernel, against the oracle and against each other bit for bit."""
+    steps_log2 = [0.0, 7.5, 7.9, 8.5, 0.3, 200.0, -150.0, 7.99, 8.01, -30.0]  # increments per tile
+    level = np.cumsum(steps_log2) * np.log(2.0)  # natural-log logit of each tile
+    n = 64 * len(level)
+    for heads, reps in ((1, 1), (3, 3)):
+        w = make_custom([n] * reps, heads, 128, seed=29, scale=1.0)
+        qf = np.zeros((n * reps, heads, 128), dtype=np.float32)
+        qf[:, :, 0] = 1.0  # logit of (query, key) = K[key, 0]
+        kf = np.zeros((n * reps, heads, 128), dtype=np.float32)
+        kf[:, :, 0] = np.tile(np.repeat(level, 64), reps)[:, None]
+        w.q, w.k = f32_to_bf16_bits(qf), f32_to_bf16_bits(kf)
+        ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+        outs = [runner.run(w, kernel=kern) for kern in (da.KERNEL_128, da.KERNEL_PINGPONG, da.KERNEL_WIDE)]
+        for got in outs:
+            assert_parity(got, ref, "staircase logits")
+        assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[1], outs[2])
+
+
 # ------------------------------------------------------------------ call mechanics
 
 def test_deterministic_and_plan_cache(runner):
