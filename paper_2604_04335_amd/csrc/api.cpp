@@ -215,7 +215,7 @@ int64_t dit_attn_plan(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads
   const int rc = check_shape_args(cu_seqlens, n_seqs, n_heads, head_dim, msg);
   if (rc != DIT_ATTN_OK) return rc;
   if (capacity_items > 0 && !items) return DIT_ATTN_ERR_NULL;
-  const dit::AttnKernel kernel = dit::attn_fwd_select(cu_seqlens, n_seqs, n_heads, kMi355xComputeUnits);
+  const dit::AttnKernel kernel = dit::attn_fwd_select(cu_seqlens, nullptr, n_seqs, n_heads, kMi355xComputeUnits);
   const int bm = dit::attn_fwd_block_m(kernel);
   if (block_m) *block_m = bm;
   std::vector<dit::WorkItem> list;
@@ -264,7 +264,7 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
   CachedPlan* plan = nullptr;
   const size_t cu_n = static_cast<size_t>(n_seqs) + 1;
   const dit::AttnKernel kernel = ctx->force_kernel >= 0 ? static_cast<dit::AttnKernel>(ctx->force_kernel)
-                                                        : dit::attn_fwd_select(cu_seqlens, n_seqs, n_heads, ctx->n_cus);
+                                                        : dit::attn_fwd_select(cu_seqlens, cu_k, n_seqs, n_heads, ctx->n_cus);
   // Split-KV (opt-in): a pack of the 128-row kernel with fewer items than compute units cuts every sequence's keys into
   // chunks of at least four key tiles, as many as it takes to reach two items per compute unit, and merges the parts.
   int32_t n_splits = 1;

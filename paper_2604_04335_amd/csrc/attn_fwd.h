@@ -39,7 +39,9 @@ struct AttnParams {
 enum class AttnKernel : int { kIndependent128 = 0, kPingPong256 = 1, kWide256 = 2 };
 
 // Which kernel a pack runs on a device with n_cus compute units (a pure function of the pack).
-AttnKernel attn_fwd_select(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int n_cus);
+// cu_seqlens_k == nullptr: keys share the query boundaries.
+AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_k, int32_t n_seqs, int32_t n_heads,
+                           int n_cus);
 
 // Query rows per work item and resident workgroups per compute unit of a kernel.
 int attn_fwd_block_m(AttnKernel kernel);

@@ -230,18 +230,30 @@ static hipError_t launch_t(const AttnParams& p, int grid, hipStream_t stream) {
 int attn_fwd_block_m(AttnKernel kernel) { return kernel == AttnKernel::kIndependent128 ? 128 : 256; }
 int attn_fwd_wgs_per_cu(AttnKernel kernel) { return kernel == AttnKernel::kIndependent128 ? 2 : 1; }
 
-AttnKernel attn_fwd_select(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int n_cus) {
+AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_k, int32_t n_seqs, int32_t n_heads,
+                           int n_cus) {
   // Measured on MI355X with equal-length sequences (time of the 128-row kernel over the ping-pong kernel, by 256-row
   // items per compute unit): 0.5: 0.91;  0.75: 1.19;  0.94: 1.17;  1.0: 1.12;  1.25: 0.90;  1.5: 0.95;  1.6: 1.05;
   // 1.9: 1.10;  2.0: 1.10;  2.5: 0.96;  3.0: 1.15;  3.2: 1.02;  4 and more: 1.05-1.09.  The ping-pong kernel is ahead
   // whenever its items fill the compute units; the 128-row kernel, whose items are half as long, when there is well
   // under one 256-row item per compute unit or when the last round of 256-row items would be less than half full.
+  // Items with few key tiles (cross-attention against a few hundred text keys) also run better on the 128-row kernel,
+  // whose workgroups have no idle phase at the ends of an item: 128 keys +17 %, 256 +9 %, 512 +3 %, 1024 -4 %.  (Packs
+  // of short self-attention sequences do not follow: 256 and 512 tokens -2 %, 640 +4 %, 768 -4 %; they stay as they are.)
   // Of the 256-row kernels the ping-pong one is ahead of the wide one at every sequence length once the chip has
   // warmed up (6-10 % at head dimension 128, 0-4 % at 64); measured on a cold chip, in the first ~20 ms after idle,
   // whichever kernel runs second looks faster.
-  int64_t items256 = 0;
-  for (int32_t i = 0; i < n_seqs; ++i) items256 += (int64_t)((cu_seqlens[i + 1] - cu_seqlens[i] + 255) / 256) * n_heads;
+  const int32_t* ck = cu_seqlens_k ? cu_seqlens_k : cu_seqlens;
+  int64_t items256 = 0, tiles = 0;
+  for (int32_t i = 0; i < n_seqs; ++i) {
+    const int64_t lq = cu_seqlens[i + 1] - cu_seqlens[i], lk = ck[i + 1] - ck[i];
+    if (lq == 0 || lk == 0) continue;
+    const int64_t it = (lq + 255) / 256 * n_heads;
+    items256 += it;
+    tiles += it * ((lk + 63) / 64);
+  }
   if (items256 * 8 < (int64_t)n_cus * 5) return AttnKernel::kIndependent128;
+  if (cu_seqlens_k != nullptr && tiles <= 10 * items256) return AttnKernel::kIndependent128;
   const int64_t in_last_round = items256 % n_cus;
   if (items256 <= 3 * (int64_t)n_cus && in_last_round != 0 && 2 * in_last_round <= n_cus) return AttnKernel::kIndependent128;
   return AttnKernel::kPingPong256;
