@@ -120,18 +120,27 @@ HBM_PEAK_GBS = 8000.0
 
 
 def _time_calls(torch, fn, steps, warmup):
+    """Mean milliseconds per call of a sub-millisecond operation.  `steps` calls are too short a sample for those (20
+    calls of a 0.4 ms kernel read 15 % slow right after the warm-up), so the timed region is stretched to 50 ms."""
     _prewarm(torch, fn)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    for i in range(steps):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    n = max(steps, min(5000, int(50.0 / max(e0.elapsed_time(e1) / 5, 1e-3)) + 1))
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+    for i in range(n):
         starts[i].record()
         fn()
         ends[i].record()
     torch.cuda.synchronize()
-    return float(np.mean([s.elapsed_time(e) for s, e in zip(starts, ends)]))
+    return float(np.mean([s.elapsed_time(e) for s, e in zip(starts, ends)])), n
 
 
 def bench_other(da, torch, ctx, args):
@@ -146,11 +155,11 @@ def bench_other(da, torch, ctx, args):
         lses = [torch.randn((T, H), device="cuda", generator=g) * 3 for _ in range(P)]
         out = torch.empty_like(parts[0])
         lse = torch.empty_like(lses[0])
-        ms = _time_calls(torch, lambda: da.dit_attn_merge(ctx, parts, lses, T, H, D, out, lse, stream), args.steps, args.warmup)
+        ms, timed = _time_calls(torch, lambda: da.dit_attn_merge(ctx, parts, lses, T, H, D, out, lse, stream), args.steps, args.warmup)
         nbytes = (P + 1) * (T * H * D * 2 + T * H * 4)
         gbs = nbytes / (ms * 1e-3) / 1e9
         return {"metric": "partial-result merge, GB/s of algorithmic HBM traffic, 1 GPU", "value": round(gbs, 1), "unit": "GB/s",
-                "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+                "n_gpus": 1, "steps": timed, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
                 "dtype": "bf16", "data": "synthetic", "config": {"workload": "merge of 4 parts, 49178 rows x 24 heads x 128"},
                 "roofline": {"bound": "hbm", "kernel": "merge_kernel<4>", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_hbm_bytes": nbytes}}
@@ -165,11 +174,11 @@ def bench_other(da, torch, ctx, args):
         def both():
             da.dit_attn_sp_pack_heads(ctx, x, y, n, Hh, D, p, stream)
             da.dit_attn_sp_unpack_heads(ctx, y, z, n, Hh, D, p, stream)
-        ms = _time_calls(torch, both, args.steps, args.warmup)
+        ms, timed = _time_calls(torch, both, args.steps, args.warmup)
         nbytes = 2 * 2 * n * Hh * D * 2
         gbs = nbytes / (ms * 1e-3) / 1e9
         return {"metric": "head-split layout pack + unpack, GB/s of algorithmic HBM traffic, 1 GPU", "value": round(gbs, 1),
-                "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+                "unit": "GB/s", "n_gpus": 1, "steps": timed, "warmup": args.warmup, "ms_per_step": round(ms, 4),
                 "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
                 "config": {"workload": "pack then unpack of [19028, 40, 128], sp degree 4"},
                 "roofline": {"bound": "hbm", "kernel": "sp_layout_kernel<true> + sp_layout_kernel<false>", "achieved": round(gbs, 1),
@@ -180,13 +189,13 @@ def bench_other(da, torch, ctx, args):
     w = make_cross(q_lens, k_lens, H, D, seed=2001)
     q, k, v = _to_dev(w.q, torch), _to_dev(w.k, torch), _to_dev(w.v, torch)
     out = torch.empty_like(q)
-    ms = _time_calls(torch, lambda: da.dit_attn_cross_varlen_fwd(ctx, q, k, v, w.cu_seqlens_q, w.cu_seqlens_k, H, D, w.scale, out,
+    ms, timed = _time_calls(torch, lambda: da.dit_attn_cross_varlen_fwd(ctx, q, k, v, w.cu_seqlens_q, w.cu_seqlens_k, H, D, w.scale, out,
                                                                None, stream), args.steps, args.warmup)
     flops = 4.0 * H * D * float(sum(a * b for a, b in zip(q_lens, k_lens)))
     tf = flops / (ms * 1e-3) / 1e12
     clock_mhz, _ = da.dit_attn_last_launch_clock(ctx)
     return {"metric": "DiT cross-attention TFLOP/s (bf16), 1 GPU", "value": round(tf, 2), "unit": "TFLOP/s", "n_gpus": 1,
-            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "dtype": "bf16",
+            "steps": timed, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "dtype": "bf16",
             "data": "synthetic", "config": {"workload": "6x4352 + 20506 latent queries against 512 text keys each, 24 heads, head_dim 128"},
             "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "shader_clock_mhz": round(clock_mhz, 1),
