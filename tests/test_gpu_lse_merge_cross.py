@@ -152,6 +152,31 @@ def test_merge_kernel_against_oracle_on_random_parts(ctx, n_parts, head_dim):
         assert np.all(got[9, 1] == 0.0)
 
 
+def test_merge_beyond_four_gib(ctx):
+    """Two parts of 2.3e9 elements (4.6 GB) each: the merge kernel's chunk and byte offsets pass 2^32.  Device-side
+    seeded parts; the oracle merges sampled rows, among them the rows on either side of the 4 GiB line and the last."""
+    T, H, D = 16500, 1100, 128
+    assert T * H * D * 2 > 2 ** 32
+    print(f"merge beyond 4 GiB: T={T} H={H} D={D}", flush=True)
+    gen = torch.Generator(device="cuda").manual_seed(505)
+    outs = [torch.empty((T, H, D), dtype=torch.bfloat16, device="cuda").normal_(generator=gen) for _ in range(2)]
+    lses = [torch.empty((T, H), dtype=torch.float32, device="cuda").normal_(std=3.0, generator=gen) for _ in range(2)]
+    out = torch.empty_like(outs[0])
+    lo = torch.empty((T, H), dtype=torch.float32, device="cuda")
+    da.dit_attn_merge(ctx, outs, lses, T, H, D, out, lo, _stream())
+    torch.cuda.synchronize()
+    line = 2 ** 32 // (H * D * 2)
+    rows = np.unique(np.concatenate([np.linspace(0, T - 1, 24).astype(int), [line - 1, line, line + 1, T - 2]]))
+    rt = torch.from_numpy(rows).cuda()
+    o64 = np.stack([widen(to_bits(o[rt])) for o in outs])
+    l64 = np.stack([l[rt].cpu().numpy().astype(np.float64) for l in lses])
+    ref_o, ref_l = orc.merge_partials(o64, l64)
+    got = widen(to_bits(out[rt]))
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got - ref_o)) <= MAX_ABS_TOL and np.sqrt(np.sum((got - ref_o) ** 2) / np.sum(ref_o ** 2)) <= REL_L2_TOL
+    assert np.max(np.abs(lo[rt].cpu().numpy().astype(np.float64) - ref_l)) <= LSE_TOL
+
+
 @pytest.mark.parametrize("q_lens,k_lens,H,D", [
     ([300, 5, 129], [77, 226, 1], 3, 128),          # ragged, keys shorter than one tile
     ([1000, 0, 64, 200], [226, 50, 0, 512], 2, 64),  # a sequence without queries, one without keys

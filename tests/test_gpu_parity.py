@@ -104,6 +104,43 @@ def test_full_size_configs_sampled_rows(runner, name, max_rows):
             assert np.all(gf[s:e] >= lo[None] - 1e-6) and np.all(gf[s:e] <= hi[None] + 1e-6)
 
 
+def test_tensors_beyond_four_gib(runner):
+    """Maximum sizes: 2.3e9 elements and 4.6 GB per tensor, so element indices pass 2^31 and byte offsets pass 2^32
+    inside the pack.  Three heads (first, middle, last) hold the seeded generator's data and are checked against the
+    oracle on sampled rows of every sequence, the last of which lies wholly above 4 GiB; the other heads hold
+    device-side seeded noise and are checked for the convex-hull property on a stretch of rows."""
+    lens, H, D = [9000, 6700, 800], 1100, 128
+    heads = [0, 547, H - 1]
+    w = make_custom(lens, len(heads), D, seed=77)
+    cu, T = w.cu_seqlens, int(w.cu_seqlens[-1])
+    assert T * H * D > 2 ** 31 and int(cu[2]) * H * D * 2 > 2 ** 32
+    _say(f"large tensors: T={T} H={H} D={D}, {T * H * D * 2 / 2**30:.2f} GiB each; filling")
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    dev = []
+    for bits in (w.q, w.k, w.v):
+        t = torch.empty((T, H, D), dtype=torch.bfloat16, device="cuda")
+        t.normal_(generator=gen)
+        t[:, heads, :] = to_dev(bits)
+        dev.append(t)
+    _say("large tensors: running GPU")
+    out = runner.run_dev(dev[0], dev[1], dev[2], cu, H, D, w.scale)
+    rows = sample_rows(cu, seed=77, block=64, max_rows=240)
+    got = to_bits(out[torch.from_numpy(rows).cuda()][:, heads, :])
+    _say(f"large tensors: oracle on {len(rows)} rows x {len(heads)} heads")
+    ref = orc.attention_varlen_rows(w.q, w.k, w.v, cu, w.scale, rows)
+    max_abs, rel = assert_parity(got, ref, "large tensors")
+    _say(f"large tensors: max_abs={max_abs:.3e} rel_l2={rel:.3e}")
+    for i in range(len(lens)):
+        sel = np.nonzero((rows >= cu[i]) & (rows < cu[i + 1]))[0]
+        assert_parity(got[sel], ref[sel], f"large tensors seq {i}")
+    # every head of the last sequence (all of it above 4 GiB): outputs inside the hull of that sequence's values
+    s, e = int(cu[2]), int(cu[3])
+    vf, of = dev[2][s:e].float(), out[s:e].float()
+    assert bool(torch.isfinite(of).all())
+    lo, hi = vf.amin(dim=0, keepdim=True), vf.amax(dim=0, keepdim=True)
+    assert bool(((of >= lo - 1e-6) & (of <= hi + 1e-6)).all())
+
+
 # ------------------------------------------------------------------ invariants, on the GPU
 
 def test_one_token_sequences_return_v_bits(runner):

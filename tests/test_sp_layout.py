@@ -82,6 +82,35 @@ def test_gpu_pack_unpack_bit_exact(p, n, H, D):
 
 
 @pytest.mark.gpu
+def test_gpu_pack_unpack_beyond_four_gib():
+    """2.3e9 elements, 4.6 GB: chunk indices pass 2^28 and byte offsets 2^32.  Device-side seeded bit patterns; the
+    oracle checks sampled rows (the first, the last, and rows on either side of the 4 GiB line), the round trip every bit."""
+    import torch
+    import paper_2604_04335_amd as da
+    p, n, H, D = 4, 16500, 1100, 128
+    assert n * H * D * 2 > 2 ** 32
+    print(f"layout beyond 4 GiB: n={n} H={H} D={D} p={p}", flush=True)
+    ctx = da.dit_attn_create(0)
+    try:
+        gen = torch.Generator(device="cuda").manual_seed(404)
+        xd = torch.randint(-32768, 32767, (n, H, D), dtype=torch.int16, device="cuda", generator=gen)
+        packed = torch.full((p, n, H // p, D), 0x7FC1, dtype=torch.int16, device="cuda")
+        back = torch.full_like(xd, 0x7FC1)
+        st = torch.cuda.current_stream().cuda_stream
+        da.dit_attn_sp_pack_heads(ctx, xd, packed, n, H, D, p, st)
+        da.dit_attn_sp_unpack_heads(ctx, packed, back, n, H, D, p, st)
+        torch.cuda.synchronize()
+        line = 2 ** 32 // (H * D * 2)
+        rows = np.unique(np.concatenate([np.linspace(0, n - 1, 40).astype(int), [line - 1, line, line + 1, n - 2]]))
+        rt = torch.from_numpy(rows).cuda()
+        want = lay.pack_heads(xd[rt].cpu().numpy(), p)
+        assert np.array_equal(packed[:, rt].cpu().numpy(), want)
+        assert torch.equal(back, xd)
+    finally:
+        da.dit_attn_destroy(ctx)
+
+
+@pytest.mark.gpu
 def test_gpu_layout_errors():
     import torch
     import paper_2604_04335_amd as da
