@@ -141,6 +141,26 @@ def test_tensors_beyond_four_gib(runner):
     assert bool(((of >= lo - 1e-6) & (of <= hi + 1e-6)).all())
 
 
+def test_largest_head_count(runner):
+    """65535 heads, the most the work-list's 16-bit head field and the argument check allow: first, middle and last
+    head against the oracle (seeded generator data there, device-side seeded noise elsewhere)."""
+    lens, H, D = [70, 3, 130], 65535, 64
+    heads = [0, 32768, H - 1]
+    w = make_custom(lens, len(heads), D, seed=78)
+    cu, T = w.cu_seqlens, int(w.cu_seqlens[-1])
+    _say(f"largest head count: T={T} H={H} D={D}")
+    gen = torch.Generator(device="cuda").manual_seed(78)
+    dev = []
+    for bits in (w.q, w.k, w.v):
+        t = torch.empty((T, H, D), dtype=torch.bfloat16, device="cuda").normal_(generator=gen)
+        t[:, heads, :] = to_dev(bits)
+        dev.append(t)
+    out = runner.run_dev(dev[0], dev[1], dev[2], cu, H, D, w.scale)
+    ref = orc.attention_varlen(w.q, w.k, w.v, cu, w.scale)
+    assert_parity(to_bits(out[:, heads, :]), ref, "largest head count")
+    assert bool(torch.isfinite(out.float()).all())
+
+
 # ------------------------------------------------------------------ invariants, on the GPU
 
 def test_one_token_sequences_return_v_bits(runner):
