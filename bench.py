@@ -55,7 +55,12 @@ def _prewarm(torch, step):
 
 
 def time_workload(da, torch, ctx, w, steps: int, warmup: int, zero_operands: bool = False):
-    """Returns (wall ms per step, mean kernel ms from per-step event pairs, list of per-step ms, out tensor)."""
+    """Returns (wall ms per step, mean kernel ms from per-step event pairs, list of per-step ms, host-side call times).
+
+    The last is {"first_call_host_ms", "cached_call_host_us"}: what the call itself takes on the host the first time a
+    pack is seen (work-list built, device buffer allocated, list uploaded, kernel enqueued) and once the plan is cached
+    (argument checks, cache lookup, enqueue); a process's very first call also loads the kernels' code object.  Neither
+    is part of the timed steps' kernel time."""
     q, k, v = _to_dev(w.q, torch), _to_dev(w.k, torch), _to_dev(w.v, torch)
     if zero_operands:  # same launch, same instruction stream; only the switching activity of the operands differs
         q, k, v = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
@@ -66,9 +71,19 @@ def time_workload(da, torch, ctx, w, steps: int, warmup: int, zero_operands: boo
     def step():
         da.dit_attn_varlen_fwd(ctx, q, k, v, w.cu_seqlens, H, D, w.scale, out, stream)
 
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    step()
+    first_call_ms = (time.perf_counter() - t0) * 1e3
+    torch.cuda.synchronize()
     _prewarm(torch, step)
     for _ in range(warmup):
         step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(8):  # fewer calls than the hardware queue holds: what is timed is the host side of a call
+        step()
+    cached_call_us = (time.perf_counter() - t0) * 1e6 / 8
     torch.cuda.synchronize()
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
@@ -81,7 +96,8 @@ def time_workload(da, torch, ctx, w, steps: int, warmup: int, zero_operands: boo
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     per = [s.elapsed_time(e) for s, e in zip(starts, ends)]
-    return (t1 - t0) * 1e3 / steps, float(np.mean(per)), per, out
+    host = {"first_call_host_ms": round(first_call_ms, 3), "cached_call_host_us": round(cached_call_us, 1)}
+    return (t1 - t0) * 1e3 / steps, float(np.mean(per)), per, host
 
 
 def cpu_baseline(w, budget_s: float = 40.0):
@@ -296,7 +312,7 @@ def main():
 
     w = make_workload(args.workload, args.seed)
     flops = attention_flops(w.cu_seqlens, w.n_heads, w.head_dim)
-    wall_ms, kern_ms, per, _ = time_workload(da, torch, ctx, w, args.steps, args.warmup, args.zero_operands)
+    wall_ms, kern_ms, per, host_call = time_workload(da, torch, ctx, w, args.steps, args.warmup, args.zero_operands)
     tflops = flops / (wall_ms * 1e-3) / 1e12
     kern_tflops = flops / (kern_ms * 1e-3) / 1e12
 
@@ -304,6 +320,9 @@ def main():
     # MI355X lowers its clock under matrix load, so the share of the 2.4 GHz peak understates how busy the matrix pipe is.
     clock_mhz, _ = da.dit_attn_last_launch_clock(ctx)
     peak_at_clock = 256 * 4 * 1024 * clock_mhz * 1e6 / 1e12  # CUs x SIMDs x flop per cycle of the 32x32x16 bf16 MFMA
+    # What a register-only MFMA stream reaches on this machine right now (operands with random mantissas): the ceiling that
+    # power and clocks leave under the nominal peak.
+    ceil_tflops, ceil_mhz = da.dit_attn_mfma_ceiling(ctx, 40, 20)
 
     kernel_name = {da.KERNEL_128: "attn_fwd_kernel<Tile<%d,4,64>>", da.KERNEL_PINGPONG: "attn_fwd_pp_kernel<Tile<%d,8,64>>",
                    da.KERNEL_WIDE: "attn_fwd_wide_kernel<Tile<%d,4,64>>"}[da.dit_attn_last_launch_kernel(ctx)] % w.head_dim
@@ -346,7 +365,10 @@ def main():
             "algorithmic_hbm_bytes": int(4 * w.total_tokens * w.n_heads * w.head_dim * 2),
             "shader_clock_mhz": round(clock_mhz, 1),
             "frac_at_measured_clock": round(kern_tflops / peak_at_clock, 4) if peak_at_clock > 0 else None,
+            "mfma_only_ceiling": {"tflops": round(ceil_tflops, 1), "shader_clock_mhz": round(ceil_mhz, 1),
+                                  "frac_of_it": round(kern_tflops / ceil_tflops, 4) if ceil_tflops > 0 else None},
         },
+        "host_call": host_call,
     }
 
     if args.all:

@@ -50,6 +50,7 @@ extern "C" {
 #define DIT_ATTN_ERR_CAPACITY      (-8)  /* output buffer of dit_attn_plan too small */
 #define DIT_ATTN_ERR_KERNEL        (-9)  /* dit_attn_set_kernel: no such kernel */
 #define DIT_ATTN_ERR_PARTS         (-10) /* dit_attn_merge: n_parts outside 1..8 */
+#define DIT_ATTN_ERR_COUNT         (-11) /* dit_attn_mfma_ceiling: a launch count outside its range */
 
 typedef struct dit_attn_ctx dit_attn_ctx; /* opaque */
 
@@ -223,6 +224,25 @@ int dit_attn_last_launch_clock(dit_attn_ctx* ctx, double* shader_mhz, double* ke
  * returns DIT_ATTN_KERNEL_AUTO.
  */
 int dit_attn_last_launch_kernel(const dit_attn_ctx* ctx);
+
+/*
+ * Measurement aid: what the matrix pipes of this GPU deliver with nothing else
+ * competing, for reading the attention throughput against (the benchmark
+ * definition prices the path against the bf16 MFMA peak; that peak assumes
+ * 2.4 GHz, which the part does not hold under matrix load).  Runs a
+ * register-only stream of v_mfma_f32_32x32x16_bf16 — two wavefronts per SIMD
+ * on every compute unit, operands of unit scale with random mantissas, about
+ * 4 ms per launch — warm_launches times untimed and timed_launches times
+ * between two events on the null stream, and waits for it.
+ *   tflops      out: 2*32*32*16 flop per MFMA over the timed launches.
+ *   shader_mhz  out: the shader clock sampled inside the last launch.
+ * Either pointer may be NULL.  Allocates and frees a few hundred bytes of
+ * device memory; leaves the context's state alone.
+ * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL, DIT_ATTN_ERR_COUNT (warm_launches
+ * outside 0..1000 or timed_launches outside 1..1000) or DIT_ATTN_ERR_HIP.
+ */
+int dit_attn_mfma_ceiling(dit_attn_ctx* ctx, int32_t warm_launches, int32_t timed_launches,
+                          double* tflops, double* shader_mhz);
 
 /*
  * Text of the last error recorded in `ctx` (or of the last failed

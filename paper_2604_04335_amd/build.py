@@ -9,7 +9,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libdit_attn.so")
-SOURCES = ["api.cpp", "plan.cpp", "sched_dp.cpp", "attn_fwd.hip", "attn_fwd_wide.hip", "merge.hip", "sp_layout.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "sched_dp.cpp", "attn_fwd.hip", "attn_fwd_wide.hip", "merge.hip", "sp_layout.hip", "mfma_ceiling.hip"]
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form packed fp32 instructions.
 HIP_FLAGS = [

@@ -236,6 +236,22 @@ def test_launch_clock_sample(runner):
     assert da.dit_attn_last_launch_kernel(runner.ctx) == da.KERNEL_PINGPONG
 
 
+def test_mfma_ceiling_measurement(runner):
+    """The register-only MFMA stream: between half of the nominal bf16 peak and the peak, at a plausible clock, and
+    consistent with that clock (256 CUs x 4 SIMDs x 1024 flop per cycle); bad counts are refused."""
+    _say("mfma ceiling: 10 warm + 10 timed launches")
+    tf, mhz = da.dit_attn_mfma_ceiling(runner.ctx, 10, 10)
+    _say(f"mfma ceiling: {tf:.0f} TFLOP/s at {mhz:.0f} MHz")
+    assert 1000.0 < mhz < 2500.0
+    assert 0.5 * 2516.6 < tf < 1.01 * 2516.6
+    at_clock = 256 * 4 * 1024 * mhz * 1e6 / 1e12
+    assert 0.9 * at_clock < tf < 1.02 * at_clock
+    for warm, timed in ((-1, 1), (0, 0), (1001, 1), (0, 1001)):
+        with pytest.raises(da.DitAttnError) as e:
+            da.dit_attn_mfma_ceiling(runner.ctx, warm, timed)
+        assert e.value.code == -11
+
+
 def test_head_subset_equals_heads_of_wider_run(runner):
     """The head-split shard view: running heads [10, 20) alone equals those heads of a 40-head run."""
     w = make_custom([700], 40, 128, seed=22)

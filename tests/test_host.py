@@ -28,6 +28,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert {"dit_attn_create", "dit_attn_varlen_fwd", "dit_attn_destroy", "dit_attn_last_error",
             "dit_attn_plan", "dit_attn_version", "dit_attn_varlen_fwd_lse", "dit_attn_cross_varlen_fwd", "dit_attn_merge",
             "dit_attn_sp_pack_heads", "dit_attn_sp_unpack_heads", "dit_attn_set_kernel", "dit_attn_last_launch_clock", "dit_attn_last_launch_kernel",
+            "dit_attn_mfma_ceiling",
             "dit_sched_plan_round", "dit_sched_laxity"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
