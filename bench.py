@@ -30,9 +30,9 @@ DEFAULT_WORKLOAD = "mixed_varlen"
 # each scaled by what the same counter reads for the 1 GiB copy of --copy-calibration; the summaries and the
 # commands are under profiles/.  None where no such run has been made for the workload.
 MEASURED_HBM_BYTES = {
-    "mixed_varlen": 2_534_875_034,  # fetch 1086114.3 KiB x 2.000 + write 303235.3 KiB x 1.000
-    "sp_shard": 4_421_502_054,      # fetch 2059923.8 KiB x 2.000 + write 198025.5 KiB x 1.000
-    "t2v_single": 1_423_911_117,    # fetch 629448.4 KiB x 2.000 + write 131641.4 KiB x 1.000
+    "mixed_varlen": 2_539_472_998,  # fetch 1088351.9 KiB x 2.000 + write 303250.3 KiB x 1.000
+    "sp_shard": 4_420_876_800,      # fetch 2059734.1 KiB x 2.000 + write 197794.3 KiB x 1.000
+    "t2v_single": 1_420_685_414,    # fetch 628427.5 KiB x 2.000 + write 130533.1 KiB x 1.000
 }
 
 
