@@ -322,7 +322,11 @@ def main():
     peak_at_clock = 256 * 4 * 1024 * clock_mhz * 1e6 / 1e12  # CUs x SIMDs x flop per cycle of the 32x32x16 bf16 MFMA
     # What a register-only MFMA stream reaches on this machine right now (operands with random mantissas): the ceiling that
     # power and clocks leave under the nominal peak.
-    ceil_tflops, ceil_mhz = da.dit_attn_mfma_ceiling(ctx, 40, 20)
+    ceil_tflops, ceil_mhz = da.dit_attn_mfma_ceiling(ctx, da.MIX_MFMA_ONLY, 40, 20)
+    # The same stream with the LDS operand reads and vector instructions that this kernel shape issues per MFMA beside
+    # it (no barriers, no memory loads, no dependences): the bound for a kernel of that shape.
+    shape_mix = da.MIX_WIDE if da.dit_attn_last_launch_kernel(ctx) == da.KERNEL_WIDE else da.MIX_PINGPONG
+    mix_tflops, mix_mhz = da.dit_attn_mfma_ceiling(ctx, shape_mix, 30, 15)
 
     kernel_name = {da.KERNEL_128: "attn_fwd_kernel<Tile<%d,4,64>>", da.KERNEL_PINGPONG: "attn_fwd_pp_kernel<Tile<%d,8,64>>",
                    da.KERNEL_WIDE: "attn_fwd_wide_kernel<Tile<%d,4,64>>"}[da.dit_attn_last_launch_kernel(ctx)] % w.head_dim
@@ -367,6 +371,9 @@ def main():
             "frac_at_measured_clock": round(kern_tflops / peak_at_clock, 4) if peak_at_clock > 0 else None,
             "mfma_only_ceiling": {"tflops": round(ceil_tflops, 1), "shader_clock_mhz": round(ceil_mhz, 1),
                                   "frac_of_it": round(kern_tflops / ceil_tflops, 4) if ceil_tflops > 0 else None},
+            "kernel_shape_ceiling": {"mix": "wide" if shape_mix == da.MIX_WIDE else "pingpong", "tflops": round(mix_tflops, 1),
+                                     "shader_clock_mhz": round(mix_mhz, 1),
+                                     "frac_of_it": round(kern_tflops / mix_tflops, 4) if mix_tflops > 0 else None},
         },
         "host_call": host_call,
     }

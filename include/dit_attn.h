@@ -50,7 +50,7 @@ extern "C" {
 #define DIT_ATTN_ERR_CAPACITY      (-8)  /* output buffer of dit_attn_plan too small */
 #define DIT_ATTN_ERR_KERNEL        (-9)  /* dit_attn_set_kernel: no such kernel */
 #define DIT_ATTN_ERR_PARTS         (-10) /* dit_attn_merge: n_parts outside 1..8 */
-#define DIT_ATTN_ERR_COUNT         (-11) /* dit_attn_mfma_ceiling: a launch count outside its range */
+#define DIT_ATTN_ERR_COUNT         (-11) /* dit_attn_mfma_ceiling: mix or a launch count outside its range */
 
 typedef struct dit_attn_ctx dit_attn_ctx; /* opaque */
 
@@ -226,22 +226,43 @@ int dit_attn_last_launch_clock(dit_attn_ctx* ctx, double* shader_mhz, double* ke
 int dit_attn_last_launch_kernel(const dit_attn_ctx* ctx);
 
 /*
- * Measurement aid: what the matrix pipes of this GPU deliver with nothing else
- * competing, for reading the attention throughput against (the benchmark
- * definition prices the path against the bf16 MFMA peak; that peak assumes
- * 2.4 GHz, which the part does not hold under matrix load).  Runs a
- * register-only stream of v_mfma_f32_32x32x16_bf16 — two wavefronts per SIMD
- * on every compute unit, operands of unit scale with random mantissas, about
- * 4 ms per launch — warm_launches times untimed and timed_launches times
- * between two events on the null stream, and waits for it.
+ * Measurement aid: what the matrix pipes of this GPU deliver, alone and beside
+ * the other work of an attention tile, for reading the attention throughput
+ * against (the benchmark definition prices the path against the bf16 MFMA
+ * peak; that peak assumes 2.4 GHz, which the part does not hold under matrix
+ * load on operands with real bit activity).  Runs a register-only stream of
+ * v_mfma_f32_32x32x16_bf16 on every compute unit, operands of unit scale with
+ * random mantissas, about 4-7 ms per launch, with this beside each MFMA:
+ *   DIT_ATTN_MIX_MFMA_ONLY  (0)  nothing; two wavefronts per SIMD
+ *   DIT_ATTN_MIX_PINGPONG   (1)  what the ping-pong kernel issues per MFMA:
+ *                                1 KB of LDS operand reads, 3.25 vector
+ *                                instructions, one v_exp_f32
+ *   DIT_ATTN_MIX_LDS        (2)  its LDS reads only
+ *   DIT_ATTN_MIX_VALU       (3)  its vector instructions only
+ *   DIT_ATTN_MIX_64ROW      (4)  like 1 with half the LDS bytes (64 query rows
+ *                                per wavefront), two wavefronts per SIMD
+ *   DIT_ATTN_MIX_WIDE       (5)  like 4 with one wavefront per SIMD (the wide
+ *                                kernel's shape)
+ * The extra work feeds nothing into the MFMAs, and the loop has no barriers,
+ * no loads from memory and no dependent chains: each mix is an upper bound
+ * for a kernel of that shape on this machine at this moment.  The launch runs
+ * warm_launches times untimed and timed_launches times between two events on
+ * the null stream, and the call waits for it.
  *   tflops      out: 2*32*32*16 flop per MFMA over the timed launches.
  *   shader_mhz  out: the shader clock sampled inside the last launch.
  * Either pointer may be NULL.  Allocates and frees a few hundred bytes of
  * device memory; leaves the context's state alone.
- * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL, DIT_ATTN_ERR_COUNT (warm_launches
- * outside 0..1000 or timed_launches outside 1..1000) or DIT_ATTN_ERR_HIP.
+ * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL, DIT_ATTN_ERR_COUNT (mix outside
+ * 0..5, warm_launches outside 0..1000 or timed_launches outside 1..1000) or
+ * DIT_ATTN_ERR_HIP.
  */
-int dit_attn_mfma_ceiling(dit_attn_ctx* ctx, int32_t warm_launches, int32_t timed_launches,
+#define DIT_ATTN_MIX_MFMA_ONLY 0
+#define DIT_ATTN_MIX_PINGPONG  1
+#define DIT_ATTN_MIX_LDS       2
+#define DIT_ATTN_MIX_VALU      3
+#define DIT_ATTN_MIX_64ROW     4
+#define DIT_ATTN_MIX_WIDE      5
+int dit_attn_mfma_ceiling(dit_attn_ctx* ctx, int32_t mix, int32_t warm_launches, int32_t timed_launches,
                           double* tflops, double* shader_mhz);
 
 /*

@@ -39,6 +39,12 @@ __all__ = [
     "dit_attn_last_launch_clock",
     "dit_attn_last_launch_kernel",
     "dit_attn_mfma_ceiling",
+    "MIX_MFMA_ONLY",
+    "MIX_PINGPONG",
+    "MIX_LDS",
+    "MIX_VALU",
+    "MIX_64ROW",
+    "MIX_WIDE",
     "KERNEL_AUTO",
     "KERNEL_128",
     "KERNEL_PINGPONG",
@@ -123,7 +129,7 @@ def load_library() -> ctypes.CDLL:
     lib.dit_attn_last_launch_kernel.restype = ctypes.c_int
     lib.dit_attn_last_launch_kernel.argtypes = [vp]
     lib.dit_attn_mfma_ceiling.restype = ctypes.c_int
-    lib.dit_attn_mfma_ceiling.argtypes = [vp, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.dit_attn_mfma_ceiling.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.dit_attn_last_launch_clock.restype = ctypes.c_int
     lib.dit_attn_last_launch_clock.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.dit_attn_plan.restype = i64
@@ -192,11 +198,15 @@ def dit_attn_last_launch_clock(ctx):
     return mhz.value, ms.value
 
 
-def dit_attn_mfma_ceiling(ctx, warm_launches: int = 20, timed_launches: int = 20):
-    """(TFLOP/s, shader clock in MHz) of a register-only MFMA stream on every compute unit; see include/dit_attn.h."""
+MIX_MFMA_ONLY, MIX_PINGPONG, MIX_LDS, MIX_VALU, MIX_64ROW, MIX_WIDE = range(6)
+
+
+def dit_attn_mfma_ceiling(ctx, mix: int = MIX_MFMA_ONLY, warm_launches: int = 20, timed_launches: int = 20):
+    """(TFLOP/s, shader clock in MHz) of a register-only MFMA stream on every compute unit, alone or beside the LDS
+    reads and vector instructions of an attention tile (mix: one of MIX_*); see include/dit_attn.h."""
     tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
-    rc = load_library().dit_attn_mfma_ceiling(ctypes.c_void_p(ctx), int(warm_launches), int(timed_launches), ctypes.byref(tf),
-                                              ctypes.byref(mhz))
+    rc = load_library().dit_attn_mfma_ceiling(ctypes.c_void_p(ctx), int(mix), int(warm_launches), int(timed_launches),
+                                              ctypes.byref(tf), ctypes.byref(mhz))
     if rc != 0:
         raise DitAttnError(rc, dit_attn_last_error(ctx))
     return tf.value, mhz.value

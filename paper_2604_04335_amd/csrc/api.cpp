@@ -204,17 +204,18 @@ int dit_attn_last_launch_clock(dit_attn_ctx* ctx, double* shader_mhz, double* ke
   return DIT_ATTN_OK;
 }
 
-int dit_attn_mfma_ceiling(dit_attn_ctx* ctx, int32_t warm_launches, int32_t timed_launches, double* tflops,
+int dit_attn_mfma_ceiling(dit_attn_ctx* ctx, int32_t mix, int32_t warm_launches, int32_t timed_launches, double* tflops,
                           double* shader_mhz) {
   if (!ctx) return DIT_ATTN_ERR_NULL;
   ctx->error.clear();
+  if (mix < 0 || mix >= dit::kCeilingMixes)
+    return fail(ctx, DIT_ATTN_ERR_COUNT, "mix must be in 0.." + std::to_string(dit::kCeilingMixes - 1));
   if (warm_launches < 0 || warm_launches > 1000 || timed_launches < 1 || timed_launches > 1000)
     return fail(ctx, DIT_ATTN_ERR_COUNT, "warm_launches must be in 0..1000 and timed_launches in 1..1000");
   DeviceGuard guard;
   hipError_t e = guard.enter(ctx->device);
   if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
-  constexpr int kIters = 8192;  // 2 wavefronts x 8192 x 16 MFMAs x 32 cycles per SIMD: about 4 ms
-  char* mem = nullptr;          // [2 x uint64 clock sample][64 floats]
+  char* mem = nullptr;  // [2 x uint64 clock sample][64 floats]
   hipEvent_t ev[2] = {nullptr, nullptr};
   float ms = 0.f;
   uint64_t sample[2] = {0, 0};
@@ -224,7 +225,7 @@ int dit_attn_mfma_ceiling(dit_attn_ctx* ctx, int32_t warm_launches, int32_t time
   for (int32_t i = 0; i < warm_launches + timed_launches && e == hipSuccess; ++i) {
     if (i == warm_launches) e = hipEventRecord(ev[0], nullptr);
     if (e == hipSuccess)
-      e = dit::mfma_ceiling_launch(reinterpret_cast<uint64_t*>(mem), reinterpret_cast<float*>(mem + 16), kIters, ctx->n_cus, nullptr);
+      e = dit::mfma_ceiling_launch(mix, reinterpret_cast<uint64_t*>(mem), reinterpret_cast<float*>(mem + 16), ctx->n_cus, nullptr);
   }
   if (e == hipSuccess) e = hipEventRecord(ev[1], nullptr);
   if (e == hipSuccess) e = hipEventSynchronize(ev[1]);
@@ -234,8 +235,8 @@ int dit_attn_mfma_ceiling(dit_attn_ctx* ctx, int32_t warm_launches, int32_t time
   if (ev[1]) (void)hipEventDestroy(ev[1]);
   if (mem) (void)hipFree(mem);
   if (e != hipSuccess) return fail_hip(ctx, e, "matrix-pipe ceiling measurement");
-  const double flop = static_cast<double>(timed_launches) * ctx->n_cus * dit::kCeilingWavesPerCu * static_cast<double>(kIters) *
-                      dit::kCeilingMfmaPerIter * dit::kCeilingFlopPerMfma;
+  const double flop = static_cast<double>(timed_launches) * ctx->n_cus * dit::kCeilingWavesPerCu *
+                      static_cast<double>(dit::kCeilingMfmaPerWave) * dit::kCeilingFlopPerMfma;
   if (tflops) *tflops = ms > 0.f ? flop / (static_cast<double>(ms) * 1e-3) * 1e-12 : 0.0;
   if (shader_mhz) *shader_mhz = sample[1] > 0 ? 100.0 * static_cast<double>(sample[0]) / static_cast<double>(sample[1]) : 0.0;
   return DIT_ATTN_OK;

@@ -238,17 +238,22 @@ def test_launch_clock_sample(runner):
 
 def test_mfma_ceiling_measurement(runner):
     """The register-only MFMA stream: between half of the nominal bf16 peak and the peak, at a plausible clock, and
-    consistent with that clock (256 CUs x 4 SIMDs x 1024 flop per cycle); bad counts are refused."""
-    _say("mfma ceiling: 10 warm + 10 timed launches")
-    tf, mhz = da.dit_attn_mfma_ceiling(runner.ctx, 10, 10)
+    consistent with that clock (256 CUs x 4 SIMDs x 1024 flop per cycle); every mix with extra work beside the MFMAs
+    is slower than the MFMAs alone and still above a third of the peak; bad arguments are refused."""
+    _say("mfma ceiling: 10 warm + 10 timed launches per mix")
+    tf, mhz = da.dit_attn_mfma_ceiling(runner.ctx, da.MIX_MFMA_ONLY, 10, 10)
     _say(f"mfma ceiling: {tf:.0f} TFLOP/s at {mhz:.0f} MHz")
     assert 1000.0 < mhz < 2500.0
     assert 0.5 * 2516.6 < tf < 1.01 * 2516.6
     at_clock = 256 * 4 * 1024 * mhz * 1e6 / 1e12
     assert 0.9 * at_clock < tf < 1.02 * at_clock
-    for warm, timed in ((-1, 1), (0, 0), (1001, 1), (0, 1001)):
+    for mix in (da.MIX_PINGPONG, da.MIX_LDS, da.MIX_VALU, da.MIX_64ROW, da.MIX_WIDE):
+        t2, m2 = da.dit_attn_mfma_ceiling(runner.ctx, mix, 10, 10)
+        _say(f"mix {mix}: {t2:.0f} TFLOP/s at {m2:.0f} MHz")
+        assert 2516.6 / 3 < t2 < tf and 1000.0 < m2 < 2500.0
+    for mix, warm, timed in ((0, -1, 1), (0, 0, 0), (0, 1001, 1), (0, 0, 1001), (-1, 1, 1), (6, 1, 1)):
         with pytest.raises(da.DitAttnError) as e:
-            da.dit_attn_mfma_ceiling(runner.ctx, warm, timed)
+            da.dit_attn_mfma_ceiling(runner.ctx, mix, warm, timed)
         assert e.value.code == -11
 
 
