@@ -30,9 +30,9 @@ DEFAULT_WORKLOAD = "mixed_varlen"
 # each scaled by what the same counter reads for the 1 GiB copy of --copy-calibration; the summaries and the
 # commands are under profiles/.  None where no such run has been made for the workload.
 MEASURED_HBM_BYTES = {
-    "mixed_varlen": 2_539_472_998,  # fetch 1088351.9 KiB x 2.000 + write 303250.3 KiB x 1.000
-    "sp_shard": 4_420_876_800,      # fetch 2059734.1 KiB x 2.000 + write 197794.3 KiB x 1.000
-    "t2v_single": 1_420_685_414,    # fetch 628427.5 KiB x 2.000 + write 130533.1 KiB x 1.000
+    "mixed_varlen": 2_541_192_806,  # fetch 1089238.9 KiB x 2.000 + write 303155.8 KiB x 1.000
+    "sp_shard": 4_419_153_408,      # fetch 2058975.5 KiB x 2.000 + write 197628.5 KiB x 1.000
+    "t2v_single": 1_413_653_197,    # fetch 625092.8 KiB x 2.000 + write 130335.1 KiB x 1.000
 }
 
 
@@ -275,6 +275,8 @@ def main():
                          "partial-result merge kernel (HBM bound) or for cross-attention against text keys")
     ap.add_argument("--zero-operands", action="store_true",
                     help="power check, not the metric: time the same launch on all-zero Q, K, V (the line says so in `data`)")
+    ap.add_argument("--no-ceiling", action="store_true",
+                    help="skip the matrix-pipe ceiling loops after the timed steps (profiles of the attention kernel alone)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device-to-device copy (a kernel of known HBM traffic, for counter scaling)")
     args = ap.parse_args()
@@ -322,11 +324,14 @@ def main():
     peak_at_clock = 256 * 4 * 1024 * clock_mhz * 1e6 / 1e12  # CUs x SIMDs x flop per cycle of the 32x32x16 bf16 MFMA
     # What a register-only MFMA stream reaches on this machine right now (operands with random mantissas): the ceiling that
     # power and clocks leave under the nominal peak.
-    ceil_tflops, ceil_mhz = da.dit_attn_mfma_ceiling(ctx, da.MIX_MFMA_ONLY, 40, 20)
-    # The same stream with the LDS operand reads and vector instructions that this kernel shape issues per MFMA beside
-    # it (no barriers, no memory loads, no dependences): the bound for a kernel of that shape.
-    shape_mix = da.MIX_WIDE if da.dit_attn_last_launch_kernel(ctx) == da.KERNEL_WIDE else da.MIX_PINGPONG
-    mix_tflops, mix_mhz = da.dit_attn_mfma_ceiling(ctx, shape_mix, 30, 15)
+    ceil_tflops = ceil_mhz = mix_tflops = mix_mhz = 0.0
+    shape_mix = da.MIX_PINGPONG
+    if not args.no_ceiling:
+        ceil_tflops, ceil_mhz = da.dit_attn_mfma_ceiling(ctx, da.MIX_MFMA_ONLY, 40, 20)
+        # The same stream with the LDS operand reads and vector instructions that this kernel shape issues per MFMA
+        # beside it (no barriers, no memory loads, no dependences): the bound for a kernel of that shape.
+        shape_mix = da.MIX_WIDE if da.dit_attn_last_launch_kernel(ctx) == da.KERNEL_WIDE else da.MIX_PINGPONG
+        mix_tflops, mix_mhz = da.dit_attn_mfma_ceiling(ctx, shape_mix, 30, 15)
 
     kernel_name = {da.KERNEL_128: "attn_fwd_kernel<Tile<%d,4,64>>", da.KERNEL_PINGPONG: "attn_fwd_pp_kernel<Tile<%d,8,64>>",
                    da.KERNEL_WIDE: "attn_fwd_wide_kernel<Tile<%d,4,64>>"}[da.dit_attn_last_launch_kernel(ctx)] % w.head_dim
@@ -369,9 +374,9 @@ def main():
             "algorithmic_hbm_bytes": int(4 * w.total_tokens * w.n_heads * w.head_dim * 2),
             "shader_clock_mhz": round(clock_mhz, 1),
             "frac_at_measured_clock": round(kern_tflops / peak_at_clock, 4) if peak_at_clock > 0 else None,
-            "mfma_only_ceiling": {"tflops": round(ceil_tflops, 1), "shader_clock_mhz": round(ceil_mhz, 1),
+            "mfma_only_ceiling": None if args.no_ceiling else {"tflops": round(ceil_tflops, 1), "shader_clock_mhz": round(ceil_mhz, 1),
                                   "frac_of_it": round(kern_tflops / ceil_tflops, 4) if ceil_tflops > 0 else None},
-            "kernel_shape_ceiling": {"mix": "wide" if shape_mix == da.MIX_WIDE else "pingpong", "tflops": round(mix_tflops, 1),
+            "kernel_shape_ceiling": None if args.no_ceiling else {"mix": "wide" if shape_mix == da.MIX_WIDE else "pingpong", "tflops": round(mix_tflops, 1),
                                      "shader_clock_mhz": round(mix_mhz, 1),
                                      "frac_of_it": round(kern_tflops / mix_tflops, 4) if mix_tflops > 0 else None},
         },
