@@ -30,7 +30,7 @@ __device__ __forceinline__ __bf16 unit_scale_value(uint32_t h) {
   return (__bf16)((float)(int32_t)(h & 0xffffu) * (1.0f / 16384.0f) - 2.0f);
 }
 
-// Per kCeilingMfmaPerIter MFMAs: LDSN ds_read_b128 (1 KB each per wavefront), VALN v_fma_f32, EXPN v_exp_f32 (+ v_mul_f32).
+// Per kCeilingMfmaPerIter MFMAs: LDSN ds_read_b128 (1 KB each per wavefront), VALN v_fma_f32, EXPN v_exp_f32.
 template <int LDSN, int VALN, int EXPN>
 __global__ void __launch_bounds__(512) mfma_ceiling_kernel(uint64_t* sample, float* sink, int iters) {
   __shared__ u32x4 lds[LDSN ? kLdsChunks : 1];
@@ -72,7 +72,7 @@ __global__ void __launch_bounds__(512) mfma_ceiling_kernel(uint64_t* sample, flo
         x[r & 7] = __builtin_fmaf(x[r & 7], m1, m2);
 #pragma unroll
       for (int r = j * EXPN / kCeilingMfmaPerIter; r < (j + 1) * EXPN / kCeilingMfmaPerIter; ++r)
-        x[r & 7] = __builtin_amdgcn_exp2f(x[r & 7]) * 0.5f;
+        x[r & 7] = __builtin_amdgcn_exp2f(-x[r & 7]);  // x -> 2^-x stays in (0, 1]; the negation is an operand modifier
     }
     if (LDSN) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   }
