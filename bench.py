@@ -27,13 +27,42 @@ MFMA_BF16_PEAK_TFLOPS = 2516.6
 DEFAULT_WORKLOAD = "mixed_varlen"
 
 # HBM bytes per launch (fetch + write) from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this file,
-# each scaled by what the same counter reads for the 1 GiB copy of --copy-calibration; the summaries and the
-# commands are under profiles/.  None where no such run has been made for the workload.
+# each scaled by what the same counter reads for the 1 GiB copy of --copy-calibration.  Counters cannot be read from
+# inside a timed run, so the figure is a constant tied to a profile: (bytes, summary under profiles/ that holds the
+# counter readings, the commands and the kernel build they were taken on).  A workload without a current profile
+# reports traffic null.
 MEASURED_HBM_BYTES = {
-    "mixed_varlen": 2_541_192_806,  # fetch 1089238.9 KiB x 2.000 + write 303155.8 KiB x 1.000
-    "sp_shard": 4_419_153_408,      # fetch 2058975.5 KiB x 2.000 + write 197628.5 KiB x 1.000
-    "t2v_single": 1_413_653_197,    # fetch 625092.8 KiB x 2.000 + write 130335.1 KiB x 1.000
+    "mixed_varlen": (2_541_192_806, "profiles/attn_fwd_pp_kernel_mixed_varlen.md"),  # fetch 1089238.9 KiB x 2.000 + write 303155.8 KiB
+    "sp_shard": (4_419_153_408, "profiles/attn_fwd_pp_kernel_sp_shard.md"),          # fetch 2058975.5 KiB x 2.000 + write 197628.5 KiB
+    "t2v_single": (1_413_653_197, "profiles/attn_fwd_pp_kernel_t2v_single.md"),      # fetch 625092.8 KiB x 2.000 + write 130335.1 KiB
 }
+# The second configuration that the benchmark definition holds to the 50 % target; timed in the default run as well
+# and reported under "second_target_config" (the headline `value` stays DEFAULT_WORKLOAD's).
+SECOND_TARGET_WORKLOAD = "sp_shard"
+
+
+def load_probe():
+    """bench.py's measurement aid (register-only MFMA loops), a library of its own beside the attention library.
+    Returns a callable (mix, warm, timed) -> (TFLOP/s, MHz), or None when it has not been built."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2604_04335_amd", "libdit_probe.so")
+    if not os.path.exists(path):
+        return None
+    lib = ctypes.CDLL(path)
+    lib.dit_probe_mfma_ceiling.restype = ctypes.c_int
+    lib.dit_probe_mfma_ceiling.argtypes = [ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+
+    def run(mix, warm, timed):
+        tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+        rc = lib.dit_probe_mfma_ceiling(0, mix, warm, timed, ctypes.byref(tf), ctypes.byref(mhz))
+        if rc != 0:
+            raise RuntimeError(f"dit_probe_mfma_ceiling returned {rc}")
+        return tf.value, mhz.value
+    return run
+
+
+PROBE_MIX_MFMA_ONLY, PROBE_MIX_PINGPONG = 0, 1
 
 
 def _to_dev(bits, torch):
@@ -259,6 +288,39 @@ def bench_sched():
             "cpu_baseline": {"value": round(oracle_us, 1), "unit": "us", "cores": 1, "kind": "oracle", "sample": "50 rounds of the same instance"}}
 
 
+KERNEL_NAMES = {0: "attn_fwd_kernel<Tile<%d,4,64,1>>", 1: "attn_fwd_pp_kernel<Tile<%d,8,64,2>>"}
+
+
+def workload_config(w, flops, split_kv):
+    return {"workload": w.name, "seq_lens": w.seq_lens, "n_heads": w.n_heads, "head_dim": w.head_dim,
+            "total_tokens": w.total_tokens, "tflop_per_call": round(flops / 1e12, 4), "seed": w.seed, "split_kv": split_kv}
+
+
+def roofline_of(da, ctx, w, kern_ms):
+    """The roofline object of the launch that was just timed on `ctx` (kern_ms: mean of the per-step event pairs)."""
+    flops = attention_flops(w.cu_seqlens, w.n_heads, w.head_dim)
+    kern_tflops = flops / (kern_ms * 1e-3) / 1e12
+    # Shader clock the chip sustained under the last timed launch (sampled inside the kernel, see include/dit_attn.h):
+    # MI355X lowers its clock under matrix load, so the share of the 2.4 GHz peak understates how busy the matrix pipe is.
+    clock_mhz, _ = da.dit_attn_last_launch_clock(ctx)
+    peak_at_clock = 256 * 4 * 1024 * clock_mhz * 1e6 / 1e12  # CUs x SIMDs x flop per cycle of the 32x32x16 bf16 MFMA
+    traffic = MEASURED_HBM_BYTES.get(w.name)
+    return {
+        "bound": "mfma",
+        "kernel": KERNEL_NAMES[da.dit_attn_last_launch_kernel(ctx)] % w.head_dim,
+        "achieved": round(kern_tflops, 2),
+        "peak": MFMA_BF16_PEAK_TFLOPS,
+        "unit": "TFLOP/s",
+        "frac": round(kern_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "traffic": traffic[0] if traffic else None,
+        "traffic_source": traffic[1] if traffic else None,
+        "kernel_ms_avg": round(kern_ms, 4),
+        "algorithmic_hbm_bytes": int(4 * w.total_tokens * w.n_heads * w.head_dim * 2),
+        "shader_clock_mhz": round(clock_mhz, 1),
+        "frac_at_measured_clock": round(kern_tflops / peak_at_clock, 4) if peak_at_clock > 0 else None,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -275,6 +337,8 @@ def main():
                          "partial-result merge kernel (HBM bound) or for cross-attention against text keys")
     ap.add_argument("--zero-operands", action="store_true",
                     help="power check, not the metric: time the same launch on all-zero Q, K, V (the line says so in `data`)")
+    ap.add_argument("--no-second", action="store_true",
+                    help="do not also time sp_shard (the second 50 % target) in a default-workload run")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the matrix-pipe ceiling loops after the timed steps (profiles of the attention kernel alone)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -316,25 +380,22 @@ def main():
     flops = attention_flops(w.cu_seqlens, w.n_heads, w.head_dim)
     wall_ms, kern_ms, per, host_call = time_workload(da, torch, ctx, w, args.steps, args.warmup, args.zero_operands)
     tflops = flops / (wall_ms * 1e-3) / 1e12
-    kern_tflops = flops / (kern_ms * 1e-3) / 1e12
+    roofline = roofline_of(da, ctx, w, kern_ms)
+    kern_tflops = roofline["achieved"]
 
-    # Shader clock the chip sustained under the last timed launch (sampled inside the kernel, see include/dit_attn.h):
-    # MI355X lowers its clock under matrix load, so the share of the 2.4 GHz peak understates how busy the matrix pipe is.
-    clock_mhz, _ = da.dit_attn_last_launch_clock(ctx)
-    peak_at_clock = 256 * 4 * 1024 * clock_mhz * 1e6 / 1e12  # CUs x SIMDs x flop per cycle of the 32x32x16 bf16 MFMA
     # What a register-only MFMA stream reaches on this machine right now (operands with random mantissas): the ceiling that
-    # power and clocks leave under the nominal peak.
-    ceil_tflops = ceil_mhz = mix_tflops = mix_mhz = 0.0
-    shape_mix = da.MIX_PINGPONG
-    if not args.no_ceiling:
-        ceil_tflops, ceil_mhz = da.dit_attn_mfma_ceiling(ctx, da.MIX_MFMA_ONLY, 40, 20)
-        # The same stream with the LDS operand reads and vector instructions that this kernel shape issues per MFMA
-        # beside it (no barriers, no memory loads, no dependences): the bound for a kernel of that shape.
-        shape_mix = da.MIX_WIDE if da.dit_attn_last_launch_kernel(ctx) == da.KERNEL_WIDE else da.MIX_PINGPONG
-        mix_tflops, mix_mhz = da.dit_attn_mfma_ceiling(ctx, shape_mix, 30, 15)
-
-    kernel_name = {da.KERNEL_128: "attn_fwd_kernel<Tile<%d,4,64>>", da.KERNEL_PINGPONG: "attn_fwd_pp_kernel<Tile<%d,8,64>>",
-                   da.KERNEL_WIDE: "attn_fwd_wide_kernel<Tile<%d,4,64>>"}[da.dit_attn_last_launch_kernel(ctx)] % w.head_dim
+    # power and clocks leave under the nominal peak; and the same stream with the LDS operand reads and vector
+    # instructions that the ping-pong kernel issues per MFMA beside it (no barriers, no memory loads, no dependences).
+    probe = None if args.no_ceiling else load_probe()
+    if probe is not None:
+        ceil_tflops, ceil_mhz = probe(PROBE_MIX_MFMA_ONLY, 40, 20)
+        mix_tflops, mix_mhz = probe(PROBE_MIX_PINGPONG, 30, 15)
+        roofline["mfma_only_ceiling"] = {"tflops": round(ceil_tflops, 1), "shader_clock_mhz": round(ceil_mhz, 1),
+                                         "frac_of_it": round(kern_tflops / ceil_tflops, 4) if ceil_tflops > 0 else None}
+        roofline["kernel_shape_ceiling"] = {"mix": "pingpong", "tflops": round(mix_tflops, 1), "shader_clock_mhz": round(mix_mhz, 1),
+                                            "frac_of_it": round(kern_tflops / mix_tflops, 4) if mix_tflops > 0 else None}
+    else:
+        roofline["mfma_only_ceiling"] = roofline["kernel_shape_ceiling"] = None
 
     result = {
         "metric": "DiT attention TFLOP/s per denoising step (bf16) and % of MFMA peak, 1 GPU",
@@ -349,45 +410,31 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "all-zero operands (power check, not the metric)" if args.zero_operands else "synthetic",
-        "config": {
-            "workload": w.name,
-            "seq_lens": w.seq_lens,
-            "n_heads": w.n_heads,
-            "head_dim": w.head_dim,
-            "total_tokens": w.total_tokens,
-            "tflop_per_call": round(flops / 1e12, 4),
-            "seed": w.seed,
-            "split_kv": args.split_kv,
-        },
+        "config": workload_config(w, flops, args.split_kv),
         "pct_of_mfma_peak": round(100.0 * tflops / MFMA_BF16_PEAK_TFLOPS, 2),
         "step_ms_min": round(float(np.min(per)), 4),
         "step_ms_cv_pct": round(100.0 * float(np.std(per) / np.mean(per)), 3),
-        "roofline": {
-            "bound": "mfma",
-            "kernel": kernel_name,
-            "achieved": round(kern_tflops, 2),
-            "peak": MFMA_BF16_PEAK_TFLOPS,
-            "unit": "TFLOP/s",
-            "frac": round(kern_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-            "traffic": MEASURED_HBM_BYTES.get(w.name),
-            "kernel_ms_avg": round(kern_ms, 4),
-            "algorithmic_hbm_bytes": int(4 * w.total_tokens * w.n_heads * w.head_dim * 2),
-            "shader_clock_mhz": round(clock_mhz, 1),
-            "frac_at_measured_clock": round(kern_tflops / peak_at_clock, 4) if peak_at_clock > 0 else None,
-            "mfma_only_ceiling": None if args.no_ceiling else {"tflops": round(ceil_tflops, 1), "shader_clock_mhz": round(ceil_mhz, 1),
-                                  "frac_of_it": round(kern_tflops / ceil_tflops, 4) if ceil_tflops > 0 else None},
-            "kernel_shape_ceiling": None if args.no_ceiling else {"mix": "wide" if shape_mix == da.MIX_WIDE else "pingpong", "tflops": round(mix_tflops, 1),
-                                     "shader_clock_mhz": round(mix_mhz, 1),
-                                     "frac_of_it": round(kern_tflops / mix_tflops, 4) if mix_tflops > 0 else None},
-        },
+        "roofline": roofline,
         "host_call": host_call,
     }
+
+    # The other configuration held to the 50 % target, in the same run (same steps and warm-up, its own event pairs).
+    if args.workload == DEFAULT_WORKLOAD and not args.zero_operands and not args.no_second:
+        w2 = make_workload(SECOND_TARGET_WORKLOAD)
+        f2 = attention_flops(w2.cu_seqlens, w2.n_heads, w2.head_dim)
+        wall2, kern2, per2, _ = time_workload(da, torch, ctx, w2, args.steps, args.warmup)
+        result["second_target_config"] = {
+            "value": round(f2 / (wall2 * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(wall2, 4), "pct_of_mfma_peak": round(100.0 * f2 / (wall2 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
+            "step_ms_min": round(float(np.min(per2)), 4), "config": workload_config(w2, f2, args.split_kv),
+            "roofline": roofline_of(da, ctx, w2, kern2)}
+        del w2
 
     if args.all:
         per_cfg = {}
         for name in CONFIG_NAMES:
             if name == w.name:
-                per_cfg[name] = {"ms": round(kern_ms, 4), "tflops": round(kern_tflops, 2)}
+                per_cfg[name] = {"ms": round(roofline["kernel_ms_avg"], 4), "tflops": round(kern_tflops, 2)}
                 continue
             w2 = make_workload(name)
             f2 = attention_flops(w2.cu_seqlens, w2.n_heads, w2.head_dim)

@@ -50,7 +50,8 @@ extern "C" {
 #define DIT_ATTN_ERR_CAPACITY      (-8)  /* output buffer of dit_attn_plan too small */
 #define DIT_ATTN_ERR_KERNEL        (-9)  /* dit_attn_set_kernel: no such kernel */
 #define DIT_ATTN_ERR_PARTS         (-10) /* dit_attn_merge: n_parts outside 1..8 */
-#define DIT_ATTN_ERR_COUNT         (-11) /* dit_attn_mfma_ceiling: mix or a launch count outside its range */
+#define DIT_ATTN_ERR_LIMIT         (-11) /* dit_attn_varlen_fwd_noalloc: the pack exceeds the fixed scratch limits */
+#define DIT_ATTN_ERR_CAPTURE       (-12) /* the stream is capturing and the call would have to allocate or copy */
 
 typedef struct dit_attn_ctx dit_attn_ctx; /* opaque */
 
@@ -89,6 +90,8 @@ int dit_attn_create(dit_attn_ctx** out_ctx, int device_id);
  * call with a new (cu_seqlens, n_heads, head_dim) builds a work-list on the host
  * and uploads it (one device allocation and one synchronous copy); later
  * calls with the same pack reuse it and do no host work beyond a compare.
+ * Under HIP graph capture only such a later call is possible (else DIT_ATTN_ERR_CAPTURE); the captured pack stays
+ * cached until the context is destroyed (see dit_attn_plan_cache_victim).
  * The caller keeps ownership of every buffer.  Validation precedes any launch:
  * on a non-zero return `out` is untouched.
  */
@@ -111,6 +114,11 @@ void dit_attn_destroy(dit_attn_ctx* ctx);
  * sequence - the ring half of the unified sequence parallelism that the paper's elastic SP builds on (Section 5,
  * Section 4.3) - hands a GPU one block of keys per step and needs exactly this pair per block.
  * lse must be 4-byte aligned and hold total_tokens * n_heads floats; everything else as dit_attn_varlen_fwd.
+ * Accuracy contract: |lse - exact| <= 4e-3.  The sum inside the logarithm is taken over the probabilities as rounded to
+ * bf16 for the second contraction (each within 2^-8 relative, all positive), so lse is within ln(1 + 2^-8) = 3.9e-3
+ * of the exact value plus ~1e-5 of fp32 arithmetic; the bound is approached only by rows that one key dominates
+ * (typically < 1e-3).  In exchange a merge that uses these lse values reproduces exactly the quotient that a single
+ * pass over all keys forms from the same rounded probabilities.
  */
 int dit_attn_varlen_fwd_lse(dit_attn_ctx* ctx,
                             const void* q, const void* k, const void* v,
@@ -166,7 +174,7 @@ int dit_attn_sp_unpack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int6
                              int32_t n_heads, int32_t head_dim, int32_t sp_degree, void* stream);
 
 /*
- * Kernel choice of a context.  The library has three kernels for the same
+ * Kernel choice of a context.  The library has two kernels for the same
  * operation (which one is fastest depends on the pack, Section 4.3 / Table 3:
  * image steps are short, video steps long):
  *     DIT_ATTN_KERNEL_AUTO   (-1) chosen per pack: the ping-pong kernel when
@@ -178,16 +186,14 @@ int dit_attn_sp_unpack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int6
  *                                 item on average
  *     DIT_ATTN_KERNEL_128     (0) 128 query rows per tile
  *     DIT_ATTN_KERNEL_PINGPONG(1) 256 rows per tile, two alternating groups
- *     DIT_ATTN_KERNEL_WIDE    (2) 256 rows per tile, 64 per wavefront
- * The three kernels do the same arithmetic in the same order: their results
- * agree bit for bit.  A forced kernel applies to later calls on
- * `ctx`; meant for tests and measurements.
+ * The kernels do the same arithmetic in the same order: their results agree
+ * bit for bit.  A forced kernel applies to later calls on `ctx`; meant for
+ * tests and measurements.
  * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL or DIT_ATTN_ERR_KERNEL.
  */
 #define DIT_ATTN_KERNEL_AUTO     (-1)
 #define DIT_ATTN_KERNEL_128        0
 #define DIT_ATTN_KERNEL_PINGPONG   1
-#define DIT_ATTN_KERNEL_WIDE       2
 int dit_attn_set_kernel(dit_attn_ctx* ctx, int kernel);
 
 /*
@@ -216,54 +222,12 @@ int dit_attn_set_split_kv(dit_attn_ctx* ctx, int max_splits);
 int dit_attn_last_launch_clock(dit_attn_ctx* ctx, double* shader_mhz, double* kernel_ms);
 
 /*
- * Which attention kernel the last forward call on `ctx` launched: one of
- * DIT_ATTN_KERNEL_128 / _PINGPONG / _WIDE (the kernel that ran: a negative
- * scale turns a wide-kernel pack into a ping-pong launch), or
- * DIT_ATTN_KERNEL_AUTO (-1) if no attention kernel has been launched yet.
- * For measurements that name the kernel they timed.  Host state only; NULL
- * returns DIT_ATTN_KERNEL_AUTO.
+ * Which attention kernel the last forward call on `ctx` launched:
+ * DIT_ATTN_KERNEL_128 or DIT_ATTN_KERNEL_PINGPONG, or DIT_ATTN_KERNEL_AUTO (-1)
+ * if no attention kernel has been launched yet.  For measurements that name
+ * the kernel they timed.  Host state only; NULL returns DIT_ATTN_KERNEL_AUTO.
  */
 int dit_attn_last_launch_kernel(const dit_attn_ctx* ctx);
-
-/*
- * Measurement aid: what the matrix pipes of this GPU deliver, alone and beside
- * the other work of an attention tile, for reading the attention throughput
- * against (the benchmark definition prices the path against the bf16 MFMA
- * peak; that peak assumes 2.4 GHz, which the part does not hold under matrix
- * load on operands with real bit activity).  Runs a register-only stream of
- * v_mfma_f32_32x32x16_bf16 on every compute unit, operands of unit scale with
- * random mantissas, about 4-7 ms per launch, with this beside each MFMA:
- *   DIT_ATTN_MIX_MFMA_ONLY  (0)  nothing; two wavefronts per SIMD
- *   DIT_ATTN_MIX_PINGPONG   (1)  what the ping-pong kernel issues per MFMA:
- *                                1 KB of LDS operand reads, 3.25 vector
- *                                instructions, one v_exp_f32
- *   DIT_ATTN_MIX_LDS        (2)  its LDS reads only
- *   DIT_ATTN_MIX_VALU       (3)  its vector instructions only
- *   DIT_ATTN_MIX_64ROW      (4)  like 1 with half the LDS bytes (64 query rows
- *                                per wavefront), two wavefronts per SIMD
- *   DIT_ATTN_MIX_WIDE       (5)  like 4 with one wavefront per SIMD (the wide
- *                                kernel's shape)
- * The extra work feeds nothing into the MFMAs, and the loop has no barriers,
- * no loads from memory and no dependent chains: each mix is an upper bound
- * for a kernel of that shape on this machine at this moment.  The launch runs
- * warm_launches times untimed and timed_launches times between two events on
- * the null stream, and the call waits for it.
- *   tflops      out: 2*32*32*16 flop per MFMA over the timed launches.
- *   shader_mhz  out: the shader clock sampled inside the last launch.
- * Either pointer may be NULL.  Allocates and frees a few hundred bytes of
- * device memory; leaves the context's state alone.
- * Returns DIT_ATTN_OK, DIT_ATTN_ERR_NULL, DIT_ATTN_ERR_COUNT (mix outside
- * 0..5, warm_launches outside 0..1000 or timed_launches outside 1..1000) or
- * DIT_ATTN_ERR_HIP.
- */
-#define DIT_ATTN_MIX_MFMA_ONLY 0
-#define DIT_ATTN_MIX_PINGPONG  1
-#define DIT_ATTN_MIX_LDS       2
-#define DIT_ATTN_MIX_VALU      3
-#define DIT_ATTN_MIX_64ROW     4
-#define DIT_ATTN_MIX_WIDE      5
-int dit_attn_mfma_ceiling(dit_attn_ctx* ctx, int32_t mix, int32_t warm_launches, int32_t timed_launches,
-                          double* tflops, double* shader_mhz);
 
 /*
  * Text of the last error recorded in `ctx` (or of the last failed
@@ -296,6 +260,18 @@ const char* dit_attn_last_error(const dit_attn_ctx* ctx);
 int64_t dit_attn_plan(const int32_t* cu_seqlens, int32_t n_seqs,
                       int32_t n_heads, int32_t head_dim,
                       int32_t* items, int64_t capacity_items, int32_t* block_m);
+
+/*
+ * Host-only: the eviction policy of a context's cache of uploaded work-lists (at most 32 packs; paper Section 4.3:
+ * dynamic batching produces many distinct packs over a serving run).  A forward call that is recorded into a HIP graph
+ * pins its pack: the recorded launch reads the pack's device work-list (and, with split-KV, the context's workspace)
+ * on every replay, so neither is freed before dit_attn_destroy; when every cached pack is pinned the cache grows
+ * instead.  A call under capture for a pack that has no cached work-list yet (or whose split-KV workspace would have
+ * to grow) returns DIT_ATTN_ERR_CAPTURE: call once outside the capture first.
+ * Given last_use[i] (a use counter) and pinned[i] (non-zero: pinned) of n cached packs, returns the index the cache
+ * evicts next: the least recently used unpinned one, or -1 if there is none (also for n < 0 or NULL arrays).
+ */
+int32_t dit_attn_plan_cache_victim(const uint64_t* last_use, const uint8_t* pinned, int32_t n);
 
 /* Library version string, e.g. "dit_attn 0.1 gfx950". */
 const char* dit_attn_version(void);

@@ -32,7 +32,8 @@ extern "C" {
 #define DIT_SCHED_OK             0
 #define DIT_SCHED_ERR_NULL      (-1)  /* a required pointer is NULL */
 #define DIT_SCHED_ERR_ARG       (-2)  /* n_gpus outside 1..32, negative counts, b_max < 1, a candidate with gpus < 0 or
-                                         > n_gpus, a mask with bits at or above n_gpus, offsets not increasing */
+                                         > n_gpus, a mask with bits at or above n_gpus, a non-zero mask whose bit count
+                                         is not `gpus`, a non-zero `reserved`, offsets not increasing */
 #define DIT_SCHED_ERR_INFEASIBLE (-3) /* some video has no candidate that fits (give every video a hold candidate) */
 
 /* One candidate of one video (Section 4.4: hold, continue, scale up / down, resume on a pool). */

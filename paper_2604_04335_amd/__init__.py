@@ -34,21 +34,14 @@ __all__ = [
     "dit_attn_destroy",
     "dit_attn_last_error",
     "dit_attn_plan",
+    "dit_attn_plan_cache_victim",
     "dit_attn_set_kernel",
     "dit_attn_set_split_kv",
     "dit_attn_last_launch_clock",
     "dit_attn_last_launch_kernel",
-    "dit_attn_mfma_ceiling",
-    "MIX_MFMA_ONLY",
-    "MIX_PINGPONG",
-    "MIX_LDS",
-    "MIX_VALU",
-    "MIX_64ROW",
-    "MIX_WIDE",
     "KERNEL_AUTO",
     "KERNEL_128",
     "KERNEL_PINGPONG",
-    "KERNEL_WIDE",
     "DitAttention",
 ]
 
@@ -67,6 +60,8 @@ ERROR_NAMES = {
     -8: "DIT_ATTN_ERR_CAPACITY",
     -9: "DIT_ATTN_ERR_KERNEL",
     -10: "DIT_ATTN_ERR_PARTS",
+    -11: "DIT_ATTN_ERR_LIMIT",
+    -12: "DIT_ATTN_ERR_CAPTURE",
 }
 
 
@@ -128,10 +123,10 @@ def load_library() -> ctypes.CDLL:
     lib.dit_attn_set_kernel.argtypes = [vp, ctypes.c_int]
     lib.dit_attn_last_launch_kernel.restype = ctypes.c_int
     lib.dit_attn_last_launch_kernel.argtypes = [vp]
-    lib.dit_attn_mfma_ceiling.restype = ctypes.c_int
-    lib.dit_attn_mfma_ceiling.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.dit_attn_last_launch_clock.restype = ctypes.c_int
     lib.dit_attn_last_launch_clock.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.dit_attn_plan_cache_victim.restype = i32
+    lib.dit_attn_plan_cache_victim.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint8), i32]
     lib.dit_attn_plan.restype = i64
     lib.dit_attn_plan.argtypes = [i32p, i32, i32, i32, i32p, i64, i32p]
     _LIB = lib
@@ -172,7 +167,7 @@ def dit_attn_create(device_id: int = 0) -> int:
     return int(h.value)
 
 
-KERNEL_AUTO, KERNEL_128, KERNEL_PINGPONG, KERNEL_WIDE = -1, 0, 1, 2
+KERNEL_AUTO, KERNEL_128, KERNEL_PINGPONG = -1, 0, 1
 
 
 def dit_attn_set_kernel(ctx, kernel: int) -> None:
@@ -198,22 +193,8 @@ def dit_attn_last_launch_clock(ctx):
     return mhz.value, ms.value
 
 
-MIX_MFMA_ONLY, MIX_PINGPONG, MIX_LDS, MIX_VALU, MIX_64ROW, MIX_WIDE = range(6)
-
-
-def dit_attn_mfma_ceiling(ctx, mix: int = MIX_MFMA_ONLY, warm_launches: int = 20, timed_launches: int = 20):
-    """(TFLOP/s, shader clock in MHz) of a register-only MFMA stream on every compute unit, alone or beside the LDS
-    reads and vector instructions of an attention tile (mix: one of MIX_*); see include/dit_attn.h."""
-    tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
-    rc = load_library().dit_attn_mfma_ceiling(ctypes.c_void_p(ctx), int(mix), int(warm_launches), int(timed_launches),
-                                              ctypes.byref(tf), ctypes.byref(mhz))
-    if rc != 0:
-        raise DitAttnError(rc, dit_attn_last_error(ctx))
-    return tf.value, mhz.value
-
-
 def dit_attn_last_launch_kernel(ctx) -> int:
-    """KERNEL_128 / KERNEL_PINGPONG / KERNEL_WIDE: the kernel the last forward call launched; KERNEL_AUTO before any."""
+    """KERNEL_128 / KERNEL_PINGPONG: the kernel the last forward call launched; KERNEL_AUTO before any."""
     return int(load_library().dit_attn_last_launch_kernel(ctypes.c_void_p(ctx)))
 
 
@@ -325,6 +306,15 @@ def dit_attn_plan(cu_seqlens, n_heads: int, head_dim: int):
     if n2 < 0:
         raise DitAttnError(int(n2), "dit_attn_plan")
     return items[:int(n2)], int(bm.value)
+
+
+def dit_attn_plan_cache_victim(last_use, pinned) -> int:
+    """Host-only: which of the cached packs (use counters, pin flags) the plan cache evicts next; -1 if all are pinned."""
+    lu = np.ascontiguousarray(last_use, dtype=np.uint64)
+    pn = np.ascontiguousarray(pinned, dtype=np.uint8)
+    assert lu.size == pn.size
+    return int(load_library().dit_attn_plan_cache_victim(lu.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
+                                                         pn.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), int(lu.size)))
 
 
 class DitAttention:

@@ -9,7 +9,10 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libdit_attn.so")
-SOURCES = ["api.cpp", "plan.cpp", "sched_dp.cpp", "attn_fwd.hip", "attn_fwd_wide.hip", "merge.hip", "sp_layout.hip", "mfma_ceiling.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "sched_dp.cpp", "attn_fwd.hip", "merge.hip", "sp_layout.hip"]
+# bench.py's measurement aid (matrix-pipe ceiling loops); a library of its own that the attention library never loads
+PROBE_LIB_PATH = os.path.join(PKG_DIR, "libdit_probe.so")
+PROBE_SOURCES = ["probe/mfma_ceiling.hip"]
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form packed fp32 instructions.
 HIP_FLAGS = [
@@ -26,13 +29,12 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every source into libdit_attn.so next to this file; returns its path."""
+def _compile(sources, lib_path: str, verbose: bool, extra_flags=()) -> str:
     cmd = [hipcc_path(), *HIP_FLAGS, *extra_flags]
-    for s in SOURCES:
+    for s in sources:
         path = os.path.join(CSRC, s)
         cmd += (["-x", "hip", path] if s.endswith((".hip", ".cpp")) else [path])
-    tmp = LIB_PATH + ".tmp"
+    tmp = lib_path + ".tmp"
     cmd += ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -44,9 +46,20 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    os.replace(tmp, LIB_PATH)
-    return LIB_PATH
+    os.replace(tmp, lib_path)
+    return lib_path
+
+
+def build_library(verbose: bool = False, extra_flags=()) -> str:
+    """Compile the attention library into libdit_attn.so next to this file; returns its path."""
+    return _compile(SOURCES, LIB_PATH, verbose, extra_flags)
+
+
+def build_probe(verbose: bool = False) -> str:
+    """Compile bench.py's measurement aid into libdit_probe.so next to this file; returns its path."""
+    return _compile(PROBE_SOURCES, PROBE_LIB_PATH, verbose)
 
 
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_probe(verbose=True))

@@ -16,7 +16,6 @@
 
 #include "attn_fwd.h"
 #include "merge.h"
-#include "mfma_ceiling.h"
 #include "plan.h"
 #include "sp_layout.h"
 
@@ -32,6 +31,7 @@ struct CachedPlan {
   std::vector<dit::WorkItem> host_items;
   dit::WorkItem* dev_items = nullptr;
   uint64_t last_use = 0;
+  bool pinned = false;  // a launch that reads dev_items was recorded into a HIP graph: never evicted
 };
 
 constexpr size_t kMaxCachedPlans = 32;
@@ -52,6 +52,8 @@ struct dit_attn_ctx {
   int max_splits = 1;           // split-KV: at most this many key chunks per sequence (dit_attn_set_split_kv); 1 = off
   float* workspace = nullptr;   // split-KV partial results and their lse
   size_t workspace_bytes = 0;
+  bool workspace_pinned = false;        // a captured graph refers to `workspace`: kept until destroy when it is outgrown
+  std::vector<float*> retired_workspaces;
   std::vector<std::unique_ptr<CachedPlan>> plans;
   std::string error;
 };
@@ -167,6 +169,7 @@ void dit_attn_destroy(dit_attn_ctx* ctx) {
       if (p->dev_items) (void)hipFree(p->dev_items);
     if (ctx->sync) (void)hipFree(ctx->sync);
     if (ctx->workspace) (void)hipFree(ctx->workspace);
+    for (float* w : ctx->retired_workspaces) (void)hipFree(w);
   }
   (void)hipGetLastError();
   delete ctx;
@@ -174,8 +177,8 @@ void dit_attn_destroy(dit_attn_ctx* ctx) {
 
 int dit_attn_set_kernel(dit_attn_ctx* ctx, int kernel) {
   if (!ctx) return DIT_ATTN_ERR_NULL;
-  if (kernel < -1 || kernel > static_cast<int>(dit::AttnKernel::kWide256))
-    return fail(ctx, DIT_ATTN_ERR_KERNEL, "kernel must be -1 (automatic), 0 (128-row), 1 (ping-pong) or 2 (wide)");
+  if (kernel < -1 || kernel > static_cast<int>(dit::AttnKernel::kPingPong256))
+    return fail(ctx, DIT_ATTN_ERR_KERNEL, "kernel must be -1 (automatic), 0 (128-row) or 1 (ping-pong)");
   ctx->force_kernel = kernel;
   return DIT_ATTN_OK;
 }
@@ -204,48 +207,15 @@ int dit_attn_last_launch_clock(dit_attn_ctx* ctx, double* shader_mhz, double* ke
   return DIT_ATTN_OK;
 }
 
-int dit_attn_mfma_ceiling(dit_attn_ctx* ctx, int32_t mix, int32_t warm_launches, int32_t timed_launches, double* tflops,
-                          double* shader_mhz) {
-  if (!ctx) return DIT_ATTN_ERR_NULL;
-  ctx->error.clear();
-  if (mix < 0 || mix >= dit::kCeilingMixes)
-    return fail(ctx, DIT_ATTN_ERR_COUNT, "mix must be in 0.." + std::to_string(dit::kCeilingMixes - 1));
-  if (warm_launches < 0 || warm_launches > 1000 || timed_launches < 1 || timed_launches > 1000)
-    return fail(ctx, DIT_ATTN_ERR_COUNT, "warm_launches must be in 0..1000 and timed_launches in 1..1000");
-  DeviceGuard guard;
-  hipError_t e = guard.enter(ctx->device);
-  if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
-  char* mem = nullptr;  // [2 x uint64 clock sample][64 floats]
-  hipEvent_t ev[2] = {nullptr, nullptr};
-  float ms = 0.f;
-  uint64_t sample[2] = {0, 0};
-  e = hipMalloc(reinterpret_cast<void**>(&mem), 16 + 64 * sizeof(float));
-  if (e == hipSuccess) e = hipEventCreate(&ev[0]);
-  if (e == hipSuccess) e = hipEventCreate(&ev[1]);
-  for (int32_t i = 0; i < warm_launches + timed_launches && e == hipSuccess; ++i) {
-    if (i == warm_launches) e = hipEventRecord(ev[0], nullptr);
-    if (e == hipSuccess)
-      e = dit::mfma_ceiling_launch(mix, reinterpret_cast<uint64_t*>(mem), reinterpret_cast<float*>(mem + 16), ctx->n_cus, nullptr);
-  }
-  if (e == hipSuccess) e = hipEventRecord(ev[1], nullptr);
-  if (e == hipSuccess) e = hipEventSynchronize(ev[1]);
-  if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[0], ev[1]);
-  if (e == hipSuccess) e = hipMemcpy(sample, mem, sizeof(sample), hipMemcpyDeviceToHost);
-  if (ev[0]) (void)hipEventDestroy(ev[0]);
-  if (ev[1]) (void)hipEventDestroy(ev[1]);
-  if (mem) (void)hipFree(mem);
-  if (e != hipSuccess) return fail_hip(ctx, e, "matrix-pipe ceiling measurement");
-  const double flop = static_cast<double>(timed_launches) * ctx->n_cus * dit::kCeilingWavesPerCu *
-                      static_cast<double>(dit::kCeilingMfmaPerWave) * dit::kCeilingFlopPerMfma;
-  if (tflops) *tflops = ms > 0.f ? flop / (static_cast<double>(ms) * 1e-3) * 1e-12 : 0.0;
-  if (shader_mhz) *shader_mhz = sample[1] > 0 ? 100.0 * static_cast<double>(sample[0]) / static_cast<double>(sample[1]) : 0.0;
-  return DIT_ATTN_OK;
-}
-
 int dit_attn_last_launch_kernel(const dit_attn_ctx* ctx) { return ctx ? ctx->last_kernel : -1; }
 
 const char* dit_attn_last_error(const dit_attn_ctx* ctx) {
   return ctx ? ctx->error.c_str() : g_create_error.c_str();
+}
+
+int32_t dit_attn_plan_cache_victim(const uint64_t* last_use, const uint8_t* pinned, int32_t n) {
+  if (n < 0 || (n > 0 && (!last_use || !pinned))) return -1;
+  return dit::plan_cache_victim(last_use, pinned, n);
 }
 
 int64_t dit_attn_plan(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int32_t head_dim, int32_t* items,
@@ -299,6 +269,12 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
   if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
   hipStream_t s = static_cast<hipStream_t>(stream);
 
+  // A call that is being recorded into a HIP graph may neither allocate nor copy synchronously, and what it records
+  // keeps reading the work-list (and the split-KV workspace) on every replay.
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  const bool capturing = hipStreamIsCapturing(s, &cap) == hipSuccess && cap == hipStreamCaptureStatusActive;
+  (void)hipGetLastError();
+
   // Plan cache: the same pack comes back for every DiT block of every step.
   CachedPlan* plan = nullptr;
   const size_t cu_n = static_cast<size_t>(n_seqs) + 1;
@@ -335,6 +311,8 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
       break;
     }
   }
+  if (!plan && capturing)
+    return fail(ctx, DIT_ATTN_ERR_CAPTURE, "the stream is capturing and this pack has no cached work-list: call once outside the capture first");
   if (!plan) {
     std::unique_ptr<CachedPlan> np;
     try {
@@ -361,17 +339,25 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
       return fail_hip(ctx, e, "hipMemcpy(work-list)");
     }
     if (ctx->plans.size() >= kMaxCachedPlans) {
-      // Evict the least recently used plan.  hipFree waits for the device, so no kernel still reads it.
-      size_t victim = 0;
-      for (size_t i = 1; i < ctx->plans.size(); ++i)
-        if (ctx->plans[i]->last_use < ctx->plans[victim]->last_use) victim = i;
-      (void)hipFree(ctx->plans[victim]->dev_items);
-      ctx->plans.erase(ctx->plans.begin() + static_cast<std::ptrdiff_t>(victim));
+      // Evict the least recently used plan that no captured graph refers to (if all are pinned the cache grows).
+      // hipFree waits for the device, so no kernel still reads the list.
+      std::vector<uint64_t> last_use;
+      std::vector<uint8_t> pinned;
+      for (auto& pl : ctx->plans) {
+        last_use.push_back(pl->last_use);
+        pinned.push_back(pl->pinned ? 1 : 0);
+      }
+      const int victim = dit::plan_cache_victim(last_use.data(), pinned.data(), static_cast<int>(last_use.size()));
+      if (victim >= 0) {
+        (void)hipFree(ctx->plans[static_cast<size_t>(victim)]->dev_items);
+        ctx->plans.erase(ctx->plans.begin() + victim);
+      }
     }
     plan = np.get();
     ctx->plans.push_back(std::move(np));
   }
   plan->last_use = ++ctx->tick;
+  if (capturing) plan->pinned = true;
 
   // Query rows of a sequence without keys: O = 0, lse = -inf (an empty sum).
   if (cu_k) {
@@ -392,7 +378,14 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
     const size_t need = static_cast<size_t>(n_splits) * static_cast<size_t>(total_q) * static_cast<size_t>(n_heads) *
                         (static_cast<size_t>(head_dim) + 1) * sizeof(float);
     if (need > ctx->workspace_bytes) {
-      if (ctx->workspace) (void)hipFree(ctx->workspace);  // waits for the device: no kernel still uses it
+      if (capturing)
+        return fail(ctx, DIT_ATTN_ERR_CAPTURE, "the stream is capturing and the split-KV workspace would have to grow: call once outside the capture first");
+      if (ctx->workspace && ctx->workspace_pinned) {
+        ctx->retired_workspaces.push_back(ctx->workspace);  // a captured graph still writes there on replay
+        ctx->workspace_pinned = false;
+      } else if (ctx->workspace) {
+        (void)hipFree(ctx->workspace);  // waits for the device: no kernel still uses it
+      }
       ctx->workspace = nullptr;
       ctx->workspace_bytes = 0;
       e = hipMalloc(reinterpret_cast<void**>(&ctx->workspace), need);
@@ -400,6 +393,7 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
       ctx->workspace_bytes = need;
     }
   }
+  if (n_splits > 1 && capturing) ctx->workspace_pinned = true;
   float* part_out = n_splits > 1 ? ctx->workspace : nullptr;
   float* part_lse = n_splits > 1 ? ctx->workspace + static_cast<size_t>(n_splits) * total_q * n_heads * head_dim : nullptr;
   if (n_splits > 1) {
@@ -436,8 +430,7 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
   p.negate = scale < 0.f ? 1 : 0;
   e = dit::attn_fwd_launch(p, plan->kernel, head_dim, grid, s);
   if (e != hipSuccess) return fail_hip(ctx, e, "kernel launch");
-  ctx->last_kernel = plan->kernel == dit::AttnKernel::kWide256 && p.negate ? static_cast<int>(dit::AttnKernel::kPingPong256)
-                                                                           : static_cast<int>(plan->kernel);
+  ctx->last_kernel = static_cast<int>(plan->kernel);
   if (n_splits > 1) {
     dit::MergeParams m{};
     for (int32_t i = 0; i < n_splits; ++i) {

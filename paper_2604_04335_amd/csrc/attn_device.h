@@ -26,10 +26,13 @@
 // distinct banks.  The swizzle is applied by choosing which global chunk a lane
 // fetches, so it costs nothing.
 //
-// O^T and the running sum are rescaled only in tiles where the maximum of some row of the wavefront
-// grows.  The reference maximum is always the true running maximum, so the largest probability of a
-// row is exactly 1 and is not perturbed by the bf16 rounding of P (a row dominated by one key then
-// returns that key's V row exactly; a stale reference would cost up to 2^-9 relative there).
+// Softmax reference.  The value subtracted in the exponent follows a row's running maximum lazily: it moves (and O^T
+// and the running sum are rescaled) only in tiles where the row's maximum exceeds it by more than 2^8 in the base-2
+// exponent, so probabilities lie in (0, 2^8] rather than (0, 1]; the quotient O / l does not depend on the reference.
+// The running sum l is taken over the probabilities as rounded to bf16 for the second contraction, so O / l is a
+// convex combination of V rows whatever the rounding did (a row dominated by one key returns that key's V row
+// exactly), and the log-sum-exp output carries at most the 2^-8 relative error of the rounded terms:
+// |lse - exact| <= ln(1 + 2^-8) = 3.9e-3.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -56,11 +59,14 @@ constexpr int kPrefetch = 4;
 // Full scheduling fence: the compiler's instruction scheduler moves nothing across it.
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-template <int D_, int NWAVES_, int BN_>
+// BN keys form one tile: the unit of the softmax (one reference-value decision per row and tile) and of the loads.
+// A K or V buffer holds SUBS consecutive tiles; the ping-pong kernel works through SUBS = 2 tiles per phase.
+template <int D_, int NWAVES_, int BN_, int SUBS_ = 1>
 struct Tile {
   static constexpr int D = D_;
   static constexpr int NWAVES = NWAVES_;
   static constexpr int BN = BN_;
+  static constexpr int SUBS = SUBS_;
   static constexpr int NT = NWAVES * 64;           // threads
   static constexpr int BM = NWAVES * 32;           // query rows per workgroup
   static constexpr int ROW_B = D * 2;              // bytes of one K/V row of one head
@@ -74,11 +80,12 @@ struct Tile {
   static constexpr int NDB = D / 32;               // 32-wide d blocks of the output
   static constexpr int NQK = NKB * NKS;            // MFMAs of S^T = K Q^T per tile
   static constexpr int NPV = NKB * 2 * NDB;        // MFMAs of O^T += V^T P^T per tile
-  // LDS: [K0][K1][V0][V1][two item slots]
+  // LDS: [K buffer 0][K buffer 1][V buffer 0][V buffer 1][two item slots], a buffer = SUBS tiles
+  static constexpr int BUF_B = SUBS * TILE_B;
   static constexpr int K_OFF = 0;
-  static constexpr int V_OFF = 2 * TILE_B;
-  static constexpr int ITEM_OFF = 4 * TILE_B;
-  static constexpr int LDS_BYTES = 4 * TILE_B + 16;
+  static constexpr int V_OFF = 2 * BUF_B;
+  static constexpr int ITEM_OFF = 4 * BUF_B;
+  static constexpr int LDS_BYTES = 4 * BUF_B + 16;
   static_assert(GROUP % 16 == 0 && BN % GROUP == 0, "load rounds must keep row%16 fixed per lane");
   static_assert(D == 64 || D == 128, "head dimension");
 
@@ -310,6 +317,94 @@ __device__ __forceinline__ void mfma_stream(lds_char* smem, int (&va_)[T::NDB], 
   SCHED_FENCE();
 }
 
+// The MFMA stream of a matrix phase of the ping-pong kernel, which works through a pair of tiles per phase:
+// O^T += V^T P^T for NPVS tiles of the V buffer addressed by va_ (tile 0, then tile 1), then S^T = K Q^T for NQKS tiles
+// of the K buffer addressed by ka_ (k-step outermost, so a Q fragment serves NQKS * NKB consecutive MFMAs).  Between
+// the two tiles' PV MFMAs the rescale that the second tile's softmax deferred is applied (grown != 0: rare), so that
+// O^T sees exactly the sequence  (O a0 + P0 V0) a1 + P1 V1  of a tile-by-tile pass.  Operand reads run PD MFMAs ahead
+// through a ring of registers, pinned in place as in mfma_stream.
+template <class T, int NPVS, int NQKS, int PD>
+__device__ __forceinline__ void pp_stream(int (&va_)[T::NDB], int (&ka_)[T::NKS], const uint32_t (&pb)[2][T::NKB][8],
+                                          const bf16x8 (&qf)[T::NKS], f32x16 (&o)[T::NDB], f32x16 (&s)[2][T::NKB],
+                                          uint64_t grown, float alpha1) {
+  static_assert(NPVS >= 0 && NPVS <= 2 && (NQKS == 0 || NQKS == 2), "tiles per phase");
+  constexpr int NPV = NPVS * T::NPV;
+  constexpr int QW = NQKS * T::NKB;  // score accumulators that a k-step cycles through
+  constexpr int N = NPV + NQKS * T::NQK;
+  bf16x8 frag[PD];
+
+  auto load_step = [&](auto jc) {
+    constexpr int J = decltype(jc)::value;
+    if constexpr (J < NPV) {
+      constexpr int sub = J / T::NPV, j = J % T::NPV, kb = j / (2 * T::NDB), u = (j / T::NDB) % 2, db = j % T::NDB;
+      lds_char* p0 = (lds_char*)(uintptr_t)(uint32_t)(va_[db] + sub * T::TILE_B + (32 * kb + 16 * u) * T::ROW_B);
+      const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0));
+      const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * T::ROW_B));
+      frag[J % PD] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    } else {
+      constexpr int q = J - NPV, ks = q / QW, sub = (q % QW) / T::NKB, kb = q % T::NKB;
+      frag[J % PD] = *(lds_bf16x8*)(uintptr_t)(uint32_t)(ka_[ks] + sub * T::TILE_B + kb * 32 * T::ROW_B);
+    }
+  };
+  auto mfma_step = [&](auto jc) {
+    constexpr int J = decltype(jc)::value;
+    if constexpr (J < NPV) {
+      constexpr int sub = J / T::NPV, j = J % T::NPV, kb = j / (2 * T::NDB), u = (j / T::NDB) % 2, db = j % T::NDB;
+      u32x4 pw = {pb[sub][kb][4 * u], pb[sub][kb][4 * u + 1], pb[sub][kb][4 * u + 2], pb[sub][kb][4 * u + 3]};
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], __builtin_bit_cast(bf16x8, pw), o[db], 0, 0, 0);
+    } else {
+      constexpr int q = J - NPV, ks = q / QW, sub = (q % QW) / T::NKB, kb = q % T::NKB;
+      if constexpr (ks == 0) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s[sub][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], qf[ks], zero, 0, 0, 0);
+      } else {
+        s[sub][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[J % PD], qf[ks], s[sub][kb], 0, 0, 0);
+      }
+    }
+  };
+  // The accumulator of MFMA J goes into an empty asm statement together with the address register of read J + PD, so
+  // that the read cannot be issued before that MFMA (see mfma_stream).
+  auto tie = [&](auto jc) {
+    (void)s;
+    (void)o;
+    constexpr int J = decltype(jc)::value;
+    constexpr int R = J + PD;
+    if constexpr (R < N) {
+      if constexpr (J < NPV) {
+        constexpr int dbj = J % T::NDB;
+        if constexpr (R < NPV) {
+          asm volatile("" : "+v"(va_[R % T::NDB]) : "v"(o[dbj]));
+        } else {
+          asm volatile("" : "+v"(ka_[(R - NPV) / QW]) : "v"(o[dbj]));
+        }
+      } else {
+        constexpr int qj = J - NPV;
+        asm volatile("" : "+v"(ka_[(R - NPV) / QW]) : "v"(s[(qj % QW) / T::NKB][qj % T::NKB]));
+      }
+    }
+  };
+  SCHED_FENCE();
+  static_for<0, (PD < N ? PD : N)>([&](auto jc) { load_step(jc); });
+  SCHED_FENCE();
+  static_for<0, N>([&](auto jc) {
+    constexpr int J = decltype(jc)::value;
+    mfma_step(jc);
+    tie(jc);
+    if constexpr (J + PD < N) load_step(IC<J + PD>{});
+    SCHED_FENCE();
+    if constexpr (NPVS == 2 && J == T::NPV - 1) {
+      if (grown != 0) {
+#pragma unroll
+        for (int db = 0; db < T::NDB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[db][i] *= alpha1;
+      }
+      SCHED_FENCE();
+    }
+  });
+  SCHED_FENCE();
+}
+
 // max(x[lane], x[lane ^ 32]) without going through LDS.  v_permlane32_swap exchanges the upper half of its first
 // register with the lower half of its second: starting from two copies of x, the first ends up with the lower
 // half-wave's values in all lanes and the second with the upper half-wave's.  Written as assembly: with the builtin
@@ -326,10 +421,17 @@ constexpr float kRescaleLog2 = 8.0f;
 
 // Online softmax of one tile: scores s -> bf16 probabilities pb (B-operand order), reference max / sum, lazy rescale.
 // Element i of block kb is key 32*kb + 8*(i/4) + 4*hh + (i%4) of the tile, for query lane%32.
-template <class T, bool TAIL>
-__device__ __forceinline__ void tile_softmax(f32x16 (&s)[T::NKB], int hh, TailRows rows, float c,
-                                             uint32_t (&pb)[T::NKB][8], f32x16 (&o)[T::NDB], float& m_ref,
-                                             float& l_run) {
+// PHASED (the ping-pong kernel) leaves two things to the matrix phase that follows: the row sums (row_sum_burst below;
+// a v_dot2c shares the matrix pipe and, issued here, would queue behind the MFMA stream that the other wavefront of the
+// SIMD runs meanwhile: about 60 cycles each instead of 5), and, with DEFER (the second tile of a pair), the rescale of
+// O^T and l, which in a tile-by-tile pass comes after the first tile's PV MFMAs and row sum.  The function returns the
+// mask of rows whose reference moved (zero: nothing to do) and, with DEFER, their factors in alpha_out (1 for rows
+// that stayed, and for every row when the mask is zero); m_ref is updated here in every variant.
+template <class T, bool TAIL, bool PHASED = false, bool DEFER = false>
+__device__ __forceinline__ uint64_t tile_softmax(f32x16 (&s)[T::NKB], int hh, TailRows rows, float c,
+                                                 uint32_t (&pb)[T::NKB][8], f32x16 (&o)[T::NDB], float& m_ref,
+                                                 float& l_run, float* alpha_out = nullptr) {
+  static_assert(PHASED || !DEFER, "a deferred rescale needs the phased row sums");
   if (TAIL) {
 #pragma unroll
     for (int kb = 0; kb < T::NKB; ++kb)
@@ -370,15 +472,21 @@ __device__ __forceinline__ void tile_softmax(f32x16 (&s)[T::NKB], int hh, TailRo
   // (Taking the probabilities first and looking for the maximum only when a sum shows that the reference was too low
   // was measured 3 % slower, although it issues twenty vector instructions fewer per tile.)
   const bool grow = (mx - m_ref) * c > kRescaleLog2;
-  if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+  const uint64_t grown = __builtin_amdgcn_ballot_w64(grow);
+  if constexpr (DEFER) *alpha_out = 1.0f;
+  if (grown != 0) {
     const float m_new = grow ? mx : m_ref;
     const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);
     m_ref = m_new;
-    l_run *= alpha;
+    if constexpr (DEFER) {
+      *alpha_out = alpha;
+    } else {
+      l_run *= alpha;
 #pragma unroll
-    for (int db = 0; db < T::NDB; ++db)
+      for (int db = 0; db < T::NDB; ++db)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    }
   }
   const float mc = m_ref * c;
 
@@ -399,12 +507,36 @@ __device__ __forceinline__ void tile_softmax(f32x16 (&s)[T::NKB], int hh, TailRo
           if (key + 1 < rows.lo || key + 1 >= rows.hi) p1 = 0.f;
         }
         pb[kb][i >> 1] = pack_bf16x2(p0, p1);
-        lsum = add_prob_pair(lsum, pb[kb][i >> 1]);
+        if constexpr (!PHASED) lsum = add_prob_pair(lsum, pb[kb][i >> 1]);
       }
       SCHED_FENCE();
     }
   }
-  l_run += lsum;
+  if constexpr (!PHASED) {
+    l_run += lsum;
+  } else {
+    // Everything above is finished here: the compiler otherwise sinks the exponentials of a tile towards their first
+    // use, which lies behind a barrier, inside the matrix phase.
+#pragma unroll
+    for (int kb = 0; kb < T::NKB; ++kb)
+      asm volatile("" : "+v"(pb[kb][0]), "+v"(pb[kb][1]), "+v"(pb[kb][2]), "+v"(pb[kb][3]), "+v"(pb[kb][4]), "+v"(pb[kb][5]),
+                        "+v"(pb[kb][6]), "+v"(pb[kb][7]));
+    asm volatile("" : "+v"(l_run), "+v"(m_ref));
+  }
+  return grown;
+}
+
+// The row sum of one tile's rounded probabilities, in the order tile_softmax adds them: one chain of v_dot2c, issued
+// back to back.  The ping-pong kernel calls it at the end of a wavefront's matrix phase, when the matrix pipe of the
+// SIMD is this wavefront's own.
+template <class T>
+__device__ __forceinline__ float row_sum_burst(const uint32_t (&pb)[T::NKB][8]) {
+  float lsum = 0.f;
+#pragma unroll
+  for (int kb = 0; kb < T::NKB; ++kb)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) lsum = add_prob_pair(lsum, pb[kb][i]);
+  return lsum;
 }
 
 // All LDS accesses of this wave are complete, then workgroup barrier.  The "memory" clobber keeps the

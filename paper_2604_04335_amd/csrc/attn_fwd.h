@@ -29,14 +29,11 @@ struct AttnParams {
   int32_t negate;           // 1 when scale < 0: the sign of Q is flipped on load
 };
 
-// Three kernels share the tile code.
+// Two kernels share the tile code.
 //   kIndependent128: 4 wavefronts, 128 query rows per item, two unsynchronised workgroups per compute unit.
 //   kPingPong256:    8 wavefronts, 256 query rows per item, one workgroup per compute unit whose two wavefront
 //                    groups alternate between the matrix and the vector phase of consecutive tiles.
-//   kWide256:        4 wavefronts of 64 query rows, 256 per item, one workgroup per compute unit; every K / V operand
-//                    read from LDS feeds two MFMAs and the softmax runs in the shadow of the wavefront's own MFMAs.
-//                    Does not take a negative scale (attn_fwd_launch runs the ping-pong kernel on the same work-list).
-enum class AttnKernel : int { kIndependent128 = 0, kPingPong256 = 1, kWide256 = 2 };
+enum class AttnKernel : int { kIndependent128 = 0, kPingPong256 = 1 };
 
 // Which kernel a pack runs on a device with n_cus compute units (a pure function of the pack).
 // cu_seqlens_k == nullptr: keys share the query boundaries.
@@ -49,9 +46,6 @@ int attn_fwd_wgs_per_cu(AttnKernel kernel);
 
 // Enqueue the forward kernel with `grid` persistent workgroups.
 hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim, int grid, hipStream_t stream);
-
-// Defined with the wide kernel.
-hipError_t attn_fwd_wide_launch(const AttnParams& p, int head_dim, int grid, hipStream_t stream);
 
 }  // namespace dit
 

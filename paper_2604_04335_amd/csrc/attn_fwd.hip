@@ -90,23 +90,27 @@ attn_fwd_kernel(AttnParams p) {
 // ---------------------------------------------------------------------------------------------
 // Kernel B (ping-pong): 8 wavefronts, 256 query rows per workgroup, one workgroup per compute unit.
 //
-// Wavefronts w and w+4 share a SIMD.  Group 0 (waves 0-3) and group 1 (waves 4-7) run the same
-// per-tile program  softmax(t) | PV(t) + QK(t+1)  but one phase apart, with a workgroup barrier
-// after every phase: while one group keeps the matrix pipe busy (32 MFMAs), the other does its
-// softmax on the vector ALU.  Phase p of an item (p = 0 after the first barrier):
-//     group 0:  QK(0) at p=0,  softmax(t) at p=2t+1,  PV(t)+QK(t+1) at p=2t+2
-//     group 1:  idle  at p=0,  QK(0) at p=1, softmax(t) at p=2t+2, PV(t)+QK(t+1) at p=2t+3
-// K(t+1) and V(t) are therefore read in phases 2t+2 and 2t+3 only; their buffers (parity of the
-// tile index) are refilled with K(t+3) / V(t+2) from phase 2t+4 on.  The pair {K(t+2), V(t+1)} is
-// issued at the start of phase 2t+2 by group 1, which is then in its vector phase, for both groups
-// (measured: +10 % over each group loading its own share, because a wavefront in its matrix phase is
-// the critical path), and awaited by group 1 at the end of phase 2t+3, before the barrier that lets
-// group 0 read it.
+// Wavefronts w and w+4 share a SIMD.  Group 0 (waves 0-3) and group 1 (waves 4-7) run the same program one phase
+// apart, with a workgroup barrier after every phase: while one group keeps the matrix pipe busy, the other does its
+// softmax on the vector ALU.  A phase works through a PAIR of consecutive 64-key tiles (a K / V buffer holds a pair):
+// half as many barriers and MFMA-stream start-ups per key as one tile per phase, which was worth 14 % fewer cycles per
+// key.  The softmax stays per tile (one reference decision per row and 64 keys, exactly as in the 128-row kernel), so
+// both kernels produce the same bits; the second tile's rescale of O^T, which in a tile-by-tile pass happens after the
+// first tile's PV MFMAs, is deferred into the matrix phase (pp_stream).  With P(t) the pair of tiles 2t, 2t+1, phase p
+// of an item (p = 0 after the first barrier):
+//     group 0:  QK(P0) at p=0,  softmax(Pt) at p=2t+1,  PV(Pt)+QK(Pt+1) at p=2t+2
+//     group 1:  idle   at p=0,  QK(P0) at p=1, softmax(Pt) at p=2t+2, PV(Pt)+QK(Pt+1) at p=2t+3
+// K(Pt+1) and V(Pt) are therefore read in phases 2t+2 and 2t+3 only; their buffers (parity of the pair index) are
+// refilled with K(Pt+3) / V(Pt+2) from phase 2t+4 on.  {K(Pt+2), V(Pt+1)} is issued at the start of phase 2t+2 by
+// group 1, which is then in its vector phase, for both groups (a wavefront in its matrix phase is the critical path
+// and issues nothing but MFMAs and operand reads), and awaited by group 1 at the end of phase 2t+3, before the barrier
+// that lets group 0 read it.  A sequence with an odd number of tiles ends in a pair of one tile; the QK MFMAs of the
+// missing tile run on whatever its buffer half holds and their scores are never read.
 // ---------------------------------------------------------------------------------------------
 template <class T>
 __global__ void __attribute__((amdgpu_flat_work_group_size(T::NT, T::NT), amdgpu_waves_per_eu(2, 2)))
 attn_fwd_pp_kernel(AttnParams p) {
-  static_assert(T::NWAVES == 8, "two groups of four wavefronts");
+  static_assert(T::NWAVES == 8 && T::SUBS == 2, "two groups of four wavefronts, two tiles per phase");
   extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
   lds_char* smem = (lds_char*)smem_generic;
   volatile uint32_t* s_item = reinterpret_cast<volatile uint32_t*>(smem_generic + T::ITEM_OFF);
@@ -130,31 +134,56 @@ attn_fwd_pp_kernel(AttnParams p) {
     if (item_idx >= p.n_items) break;
     par ^= 1;  // the next index goes to s_item[par], see below
     const ItemCtx<T> X = begin_item<T>(p, L, item_idx, row_stride_b);
-    const int kv_len = X.it.kv_len, nt = X.nt;
+    const int kv_len = X.it.kv_len, nt = X.nt;  // nt: 64-key tiles
+    const int npairs = (nt + 1) >> 1;
 
-    auto load_k = [&](int ti) {  // K(ti) -> K buffer of parity ti&1
-      tile_load_one<T>(X.kbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, L.lrow, L.kcol, L.kvoff, smem, T::K_OFF + (ti & 1) * T::TILE_B, L.wave);
+    // Tile ti of K / V -> half ti&1 of the buffer of parity (ti>>1)&1, for the rows of wavefront `wave`.
+    auto load_k = [&](int ti, int lrow, uint32_t voff, int wave) {
+      if (ti < nt)
+        tile_load_one<T>(X.kbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, lrow, L.kcol, voff, smem,
+                         T::K_OFF + ((ti >> 1) & 1) * T::BUF_B + (ti & 1) * T::TILE_B, wave);
     };
-    auto load_v = [&](int ti) {  // V(ti) -> V buffer of parity ti&1
-      tile_load_one<T>(X.vbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, L.lrow, L.vcol, L.vvoff, smem, T::V_OFF + (ti & 1) * T::TILE_B, L.wave);
+    auto load_v = [&](int ti, int lrow, uint32_t voff, int wave) {
+      if (ti < nt)
+        tile_load_one<T>(X.vbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, lrow, L.vcol, voff, smem,
+                         T::V_OFF + ((ti >> 1) & 1) * T::BUF_B + (ti & 1) * T::TILE_B, wave);
     };
-    auto load_pair = [&](int t) {  // what phases 2t+2 / 2t+3 read: K(t+1) and V(t)
-      if (t + 1 < nt) load_k(t + 1);
-      load_v(t);
+    auto load_pair = [&](int t, int lrow, uint32_t kvoff, uint32_t vvoff, int wave) {  // what phases 2t+2 / 2t+3 read
+      load_k(2 * t + 2, lrow, kvoff, wave);
+      load_k(2 * t + 3, lrow, kvoff, wave);
+      load_v(2 * t, lrow, vvoff, wave);
+      load_v(2 * t + 1, lrow, vvoff, wave);
     };
-
-    // Inside the tile loop group 1 issues the loads of both groups (its own rows and those of wave-4) at the start of
-    // its vector phase: the wavefronts that are in their matrix phase issue nothing but MFMAs and operand reads.
+    // Inside the pair loop group 1 issues the loads of both groups (its own rows and those of wave-4).  While all four
+    // tiles are whole interior tiles (every tile but the last of a sequence) their rows form one run of 2 * LPT load
+    // rounds per tensor, GROUP rows apart: the addresses come from one running pointer and the load issue, which sits
+    // on the critical path of this group's vector phase, carries no per-tile tests or multiplications.
+    const uint32_t d4 = (uint32_t)(4 * T::RPI) * (uint32_t)row_stride_b;
+    const int64_t round_b = (int64_t)T::GROUP * row_stride_b;
     auto load_pair_all = [&](int t) {
-      load_pair(t);
-      const int w2 = L.wave - 4;
-      const int lrow2 = L.lrow - 4 * T::RPI;
-      const uint32_t d = (uint32_t)(4 * T::RPI) * (uint32_t)row_stride_b;
-      if (t + 1 < nt) tile_load_one<T>(X.kbase, row_stride_b, tile_first_key<T>(t + 1, kv_len), kv_len, lrow2, L.kcol, L.kvoff - d, smem, T::K_OFF + ((t + 1) & 1) * T::TILE_B, w2);
-      tile_load_one<T>(X.vbase, row_stride_b, tile_first_key<T>(t, kv_len), kv_len, lrow2, L.vcol, L.vvoff - d, smem, T::V_OFF + (t & 1) * T::TILE_B, w2);
+      if (2 * t + 3 < nt - 1) {
+        const char* kp = X.kbase + (int64_t)(2 * t + 2) * T::BN * row_stride_b;
+        const char* vp = X.vbase + (int64_t)(2 * t) * T::BN * row_stride_b;
+        const uint32_t lk = (uint32_t)(uintptr_t)smem + T::K_OFF + ((t + 1) & 1) * T::BUF_B + (uint32_t)L.wave * 1024u;
+        const uint32_t lv = (uint32_t)(uintptr_t)smem + T::V_OFF + (t & 1) * T::BUF_B + (uint32_t)L.wave * 1024u;
+#pragma unroll
+        for (int j = 0; j < 2 * T::LPT; ++j) {
+          lds_dma_16(kp + j * round_b, L.kvoff, lk + j * T::NWAVES * 1024);
+          lds_dma_16(kp + j * round_b, L.kvoff - d4, lk + j * T::NWAVES * 1024 - 4096);
+        }
+#pragma unroll
+        for (int j = 0; j < 2 * T::LPT; ++j) {
+          lds_dma_16(vp + j * round_b, L.vvoff, lv + j * T::NWAVES * 1024);
+          lds_dma_16(vp + j * round_b, L.vvoff - d4, lv + j * T::NWAVES * 1024 - 4096);
+        }
+      } else {
+        load_pair(t, L.lrow, L.kvoff, L.vvoff, L.wave);
+        load_pair(t, L.lrow - 4 * T::RPI, L.kvoff - d4, L.vvoff - d4, L.wave - 4);
+      }
     };
-    load_k(0);
-    load_pair(0);
+    load_k(0, L.lrow, L.kvoff, L.wave);
+    load_k(1, L.lrow, L.kvoff, L.wave);
+    load_pair(0, L.lrow, L.kvoff, L.vvoff, L.wave);
 
     bf16x8 qf[T::NKS];
     load_q<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, qf);
@@ -166,43 +195,61 @@ attn_fwd_pp_kernel(AttnParams p) {
       for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
     float m_ref = -1.0e30f;  // finite, so that (m_ref - m) * 0 is 0 when scale is 0
     float l_run = 0.f;
-    f32x16 s[T::NKB];
-    uint32_t pb[T::NKB][8];
+    f32x16 s[2][T::NKB];
+    uint32_t pb[2][T::NKB][8];
     int ka[T::NKS], va[T::NDB];  // ka: K buffer the next QK reads; va: V buffer the next PV reads
     L.operand_addrs((uint32_t)(uintptr_t)smem, (uint32_t)(uintptr_t)smem, ka, va);
+    float alpha1 = 1.f;
+    uint64_t grown = 0;
 
     wait_loads();
-    wg_barrier();                  // K(0), K(1), V(0) of every wave have landed; phase 0 starts
+    wg_barrier();                  // K(P0), K(P1), V(P0) of every wave have landed; phase 0 starts
     if (group == 1) wg_barrier();  // group 1 idles in phase 0
-    mfma_stream<T, false, 0, T::NQK, kPrefetch>(smem, va, ka, pb, qf, o, s);  // QK(0)
+    pp_stream<T, 0, 2, kPrefetch>(va, ka, pb, qf, o, s, 0, 1.f);  // QK(P0)
 #pragma unroll
-    for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
+    for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::BUF_B;
     wg_barrier();
 
-    if (nt == 1 && tid == 0) s_item[par] = take_item(p);  // two barriers follow in the last tile
-    for (int t = 0; t + 1 < nt; ++t) {
-      // ---- vector phase: softmax(t), a full tile
-      if (t + 2 == nt && tid == 0) s_item[par] = take_item(p);
+    if (npairs == 1 && tid == 0) s_item[par] = take_item(p);  // two barriers follow in the last pair
+    for (int t = 0; t + 1 < npairs; ++t) {
+      // ---- vector phase: softmax of both tiles of pair t (whole tiles)
+      if (t + 2 == npairs && tid == 0) s_item[par] = take_item(p);
       if (group == 1) load_pair_all(t + 1);
-      tile_softmax<T, false>(s, L.hh, TailRows{0, T::BN}, c, pb, o, m_ref, l_run);
+      tile_softmax<T, false, true>(s[0], L.hh, TailRows{0, T::BN}, c, pb[0], o, m_ref, l_run);
+      grown = tile_softmax<T, false, true, true>(s[1], L.hh, TailRows{0, T::BN}, c, pb[1], o, m_ref, l_run, &alpha1);
       wg_barrier();
-      // ---- matrix phase: PV(t), QK(t+1)
+      // ---- matrix phase: PV(Pt), QK(Pt+1)
       __builtin_amdgcn_s_setprio(1);
-      mfma_stream<T, true, 0, T::NQK, kPrefetch>(smem, va, ka, pb, qf, o, s);
+      pp_stream<T, 2, 2, kPrefetch>(va, ka, pb, qf, o, s, grown, alpha1);
+      l_run = (l_run + row_sum_burst<T>(pb[0])) * alpha1 + row_sum_burst<T>(pb[1]);
+      asm volatile("" : "+v"(l_run));  // the sums are taken here, not behind the barrier
       __builtin_amdgcn_s_setprio(0);
 #pragma unroll
-      for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
+      for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::BUF_B;
 #pragma unroll
-      for (int db = 0; db < T::NDB; ++db) va[db] ^= T::TILE_B;
-      if (group == 1) wait_loads();  // pair t+1, issued at the start of this group's softmax(t)
+      for (int db = 0; db < T::NDB; ++db) va[db] ^= T::BUF_B;
+      if (group == 1) wait_loads();  // pair t+1, issued at the start of this group's softmax(Pt)
       wg_barrier();
     }
-    // ---- last tile: masked softmax, PV only
-    tile_softmax<T, true>(s, L.hh, tail_rows<T>(kv_len), c, pb, o, m_ref, l_run);
-    wg_barrier();
-    __builtin_amdgcn_s_setprio(1);
-    mfma_stream<T, true, 0, 0, kPrefetch>(smem, va, ka, pb, qf, o, s);
-    __builtin_amdgcn_s_setprio(0);
+    // ---- last pair: two tiles or one, the last of them masked; PV only
+    if ((nt & 1) == 0) {
+      tile_softmax<T, false, true>(s[0], L.hh, TailRows{0, T::BN}, c, pb[0], o, m_ref, l_run);
+      grown = tile_softmax<T, true, true, true>(s[1], L.hh, tail_rows<T>(kv_len), c, pb[1], o, m_ref, l_run, &alpha1);
+      wg_barrier();
+      __builtin_amdgcn_s_setprio(1);
+      pp_stream<T, 2, 0, kPrefetch>(va, ka, pb, qf, o, s, grown, alpha1);
+      l_run = (l_run + row_sum_burst<T>(pb[0])) * alpha1 + row_sum_burst<T>(pb[1]);
+      asm volatile("" : "+v"(l_run));  // the sums are taken here, not behind the barrier
+      __builtin_amdgcn_s_setprio(0);
+    } else {
+      tile_softmax<T, true, true>(s[0], L.hh, tail_rows<T>(kv_len), c, pb[0], o, m_ref, l_run);
+      wg_barrier();
+      __builtin_amdgcn_s_setprio(1);
+      pp_stream<T, 1, 0, kPrefetch>(va, ka, pb, qf, o, s, 0, 1.f);
+      l_run += row_sum_burst<T>(pb[0]);
+      asm volatile("" : "+v"(l_run));
+      __builtin_amdgcn_s_setprio(0);
+    }
     wg_barrier();
 
     store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run, m_ref);
@@ -240,9 +287,8 @@ AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_
   // Items with few key tiles (cross-attention against a few hundred text keys) also run better on the 128-row kernel,
   // whose workgroups have no idle phase at the ends of an item: 128 keys +17 %, 256 +9 %, 512 +3 %, 1024 -4 %.  (Packs
   // of short self-attention sequences do not follow: 256 and 512 tokens -2 %, 640 +4 %, 768 -4 %; they stay as they are.)
-  // Of the 256-row kernels the ping-pong one is ahead of the wide one at every sequence length once the chip has
-  // warmed up (6-10 % at head dimension 128, 0-4 % at 64); measured on a cold chip, in the first ~20 ms after idle,
-  // whichever kernel runs second looks faster.
+  // (Comparisons of two kernels must be made on a warm chip: in the first ~20 ms after idle, while the clocks still
+  // ramp, whichever kernel runs second looks faster.)
   const int32_t* ck = cu_seqlens_k ? cu_seqlens_k : cu_seqlens;
   int64_t items256 = 0, tiles = 0;
   for (int32_t i = 0; i < n_seqs; ++i) {
@@ -260,10 +306,9 @@ AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_
 }
 
 hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim, int grid, hipStream_t stream) {
-  if (kernel == AttnKernel::kWide256 && !p.negate) return attn_fwd_wide_launch(p, head_dim, grid, stream);
   if (kernel != AttnKernel::kIndependent128) {
-    if (head_dim == 128) return launch_t<Tile<128, 8, 64>, attn_fwd_pp_kernel<Tile<128, 8, 64>>>(p, grid, stream);
-    if (head_dim == 64) return launch_t<Tile<64, 8, 64>, attn_fwd_pp_kernel<Tile<64, 8, 64>>>(p, grid, stream);
+    if (head_dim == 128) return launch_t<Tile<128, 8, 64, 2>, attn_fwd_pp_kernel<Tile<128, 8, 64, 2>>>(p, grid, stream);
+    if (head_dim == 64) return launch_t<Tile<64, 8, 64, 2>, attn_fwd_pp_kernel<Tile<64, 8, 64, 2>>>(p, grid, stream);
   } else {
     if (head_dim == 128) return launch_t<Tile<128, 4, 64>, attn_fwd_kernel<Tile<128, 4, 64>>>(p, grid, stream);
     if (head_dim == 64) return launch_t<Tile<64, 4, 64>, attn_fwd_kernel<Tile<64, 4, 64>>>(p, grid, stream);

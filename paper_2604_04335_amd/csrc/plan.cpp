@@ -51,4 +51,11 @@ void plan_build_cross(const int32_t* cu_q, const int32_t* cu_k, int32_t n_seqs, 
   }
 }
 
+int plan_cache_victim(const uint64_t* last_use, const uint8_t* pinned, int n) {
+  int victim = -1;
+  for (int i = 0; i < n; ++i)
+    if (!pinned[i] && (victim < 0 || last_use[i] < last_use[victim])) victim = i;
+  return victim;
+}
+
 }  // namespace dit

@@ -40,4 +40,9 @@ void plan_build_cross(const int32_t* cu_q, const int32_t* cu_k, int32_t n_seqs, 
 // at most n_splits chunks of whole key tiles (block_n keys), and every (query tile, head) becomes one item per chunk:
 // kv_start / kv_len describe the chunk, part its index.  The parts are combined by the merge kernel.
 
+// Eviction policy of the per-context cache of uploaded work-lists: the least recently used entry among those that no
+// captured graph refers to (pinned[i] == 0); -1 when every entry is pinned (the cache then grows instead).  A launch
+// recorded into a HIP graph keeps reading its work-list on every replay, so such a list must never be freed.
+int plan_cache_victim(const uint64_t* last_use, const uint8_t* pinned, int n);
+
 }  // namespace dit

@@ -5,9 +5,20 @@
 // MFMA.  The extra work feeds nothing into the MFMAs, so their data activity is the same in every mix, and there are
 // no barriers, no loads from memory, no dependent chains and no item boundaries: each mix is an upper bound for a
 // kernel of that shape.  The attention numbers are read against these figures as well as against the nominal peak.
-#include "mfma_ceiling.h"
+//
+// This is a measurement aid of bench.py, not part of the attention library: it is built into its own shared object
+// (libdit_probe.so) with the one C entry point at the end of this file, and nothing in libdit_attn.so refers to it.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
 namespace dit {
+
+constexpr int kCeilingMfmaPerIter = 16;            // MFMAs a wavefront issues per loop iteration
+constexpr int kCeilingMfmaPerWave = 131072;        // MFMAs per wavefront at two wavefronts per SIMD (twice that at one)
+constexpr int kCeilingWavesPerCu = 8;              // two per SIMD, as in the ping-pong attention kernel
+constexpr double kCeilingFlopPerMfma = 2.0 * 32 * 32 * 16;
+constexpr int kCeilingMixes = 6;                   // mixes 0 .. 5
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -95,7 +106,11 @@ void launch(int waves_per_cu, uint64_t* sample, float* sink, int n_cus, hipStrea
 
 }  // namespace
 
-hipError_t mfma_ceiling_launch(int mix, uint64_t* sample, float* sink, int n_cus, hipStream_t stream) {
+// Every compute unit issues kCeilingWavesPerCu * kCeilingMfmaPerWave register-only MFMAs, with the LDS reads and vector
+// instructions of `mix` beside them.  sample: device, 2 x uint64, receives the shader-cycle and 100 MHz-counter
+// differences over the run of workgroup 0's first wavefront.  sink: device, >= 64 floats (never written in practice;
+// it keeps the results alive).
+static hipError_t mfma_ceiling_launch(int mix, uint64_t* sample, float* sink, int n_cus, hipStream_t stream) {
   // Per MFMA of a 32-row wavefront the ping-pong attention kernel issues 1 KB of LDS operand reads, 3.25 vector
   // instructions (of its 136 per 32 MFMAs, one fma each here) and one v_exp_f32.
   switch (mix) {
@@ -104,10 +119,63 @@ hipError_t mfma_ceiling_launch(int mix, uint64_t* sample, float* sink, int n_cus
     case 2: launch<16, 0, 0>(8, sample, sink, n_cus, stream); break;    // its LDS reads only
     case 3: launch<0, 52, 16>(8, sample, sink, n_cus, stream); break;   // its vector instructions only
     case 4: launch<8, 52, 16>(8, sample, sink, n_cus, stream); break;   // 64 query rows per wavefront: half the LDS bytes
-    case 5: launch<8, 52, 16>(4, sample, sink, n_cus, stream); break;   // the same with one wavefront per SIMD (wide kernel)
+    case 5: launch<8, 52, 16>(4, sample, sink, n_cus, stream); break;   // the same with one wavefront per SIMD
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
 }  // namespace dit
+
+// What the matrix pipes of device `device_id` deliver, alone and beside the other work of an attention tile.
+//   mix            0 MFMAs only (two wavefronts per SIMD); 1 what the ping-pong attention kernel issues per MFMA (1 KB of
+//                  LDS operand reads, 3.25 vector instructions, one v_exp_f32); 2 its LDS reads only; 3 its vector
+//                  instructions only; 4 like 1 with half the LDS bytes (64 query rows per wavefront); 5 like 4 with one
+//                  wavefront per SIMD.
+//   warm_launches  0..1000 untimed launches first;  timed_launches 1..1000 launches between two events on the null stream.
+//   tflops         out (may be NULL): 2*32*32*16 flop per MFMA over the timed launches.
+//   shader_mhz     out (may be NULL): the shader clock sampled inside the last launch.
+// Allocates and frees a few hundred bytes of device memory and waits for the launches.
+// Returns 0, -1 (argument out of range) or -2 (a HIP call failed).
+extern "C" int dit_probe_mfma_ceiling(int device_id, int32_t mix, int32_t warm_launches, int32_t timed_launches, double* tflops,
+                                      double* shader_mhz) {
+  if (mix < 0 || mix >= dit::kCeilingMixes || warm_launches < 0 || warm_launches > 1000 || timed_launches < 1 ||
+      timed_launches > 1000)
+    return -1;
+  hipDeviceProp_t prop;
+  hipError_t e = hipSetDevice(device_id);
+  if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device_id);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return -2;
+  }
+  const int n_cus = prop.multiProcessorCount;
+  char* mem = nullptr;  // [2 x uint64 clock sample][64 floats]
+  hipEvent_t ev[2] = {nullptr, nullptr};
+  float ms = 0.f;
+  uint64_t sample[2] = {0, 0};
+  e = hipMalloc(reinterpret_cast<void**>(&mem), 16 + 64 * sizeof(float));
+  if (e == hipSuccess) e = hipEventCreate(&ev[0]);
+  if (e == hipSuccess) e = hipEventCreate(&ev[1]);
+  for (int32_t i = 0; i < warm_launches + timed_launches && e == hipSuccess; ++i) {
+    if (i == warm_launches) e = hipEventRecord(ev[0], nullptr);
+    if (e == hipSuccess)
+      e = dit::mfma_ceiling_launch(mix, reinterpret_cast<uint64_t*>(mem), reinterpret_cast<float*>(mem + 16), n_cus, nullptr);
+  }
+  if (e == hipSuccess) e = hipEventRecord(ev[1], nullptr);
+  if (e == hipSuccess) e = hipEventSynchronize(ev[1]);
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[0], ev[1]);
+  if (e == hipSuccess) e = hipMemcpy(sample, mem, sizeof(sample), hipMemcpyDeviceToHost);
+  if (ev[0]) (void)hipEventDestroy(ev[0]);
+  if (ev[1]) (void)hipEventDestroy(ev[1]);
+  if (mem) (void)hipFree(mem);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return -2;
+  }
+  const double flop = static_cast<double>(timed_launches) * n_cus * dit::kCeilingWavesPerCu *
+                      static_cast<double>(dit::kCeilingMfmaPerWave) * dit::kCeilingFlopPerMfma;
+  if (tflops) *tflops = ms > 0.f ? flop / (static_cast<double>(ms) * 1e-3) * 1e-12 : 0.0;
+  if (shader_mhz) *shader_mhz = sample[1] > 0 ? 100.0 * static_cast<double>(sample[0]) / static_cast<double>(sample[1]) : 0.0;
+  return 0;
+}

@@ -82,8 +82,12 @@ int dit_sched_plan_round(int32_t n_gpus, const dit_sched_candidate* candidates, 
   const int32_t n_cand = cand_offsets[n_videos];
   if (n_cand > 0 && !candidates) return DIT_SCHED_ERR_NULL;
   const uint32_t all = n_gpus == 32 ? 0xFFFFFFFFu : ((1u << n_gpus) - 1u);
-  for (int32_t c = 0; c < n_cand; ++c)
-    if (candidates[c].gpus < 0 || candidates[c].gpus > n_gpus || (candidates[c].gpu_mask & ~all)) return DIT_SCHED_ERR_ARG;
+  for (int32_t c = 0; c < n_cand; ++c) {
+    const dit_sched_candidate& cd = candidates[c];
+    if (cd.gpus < 0 || cd.gpus > n_gpus || (cd.gpu_mask & ~all) || cd.reserved != 0) return DIT_SCHED_ERR_ARG;
+    // An anchored candidate names exactly the GPUs it counts: the GPU assignment of the image batches relies on it.
+    if (cd.gpu_mask != 0 && __builtin_popcount(cd.gpu_mask) != cd.gpus) return DIT_SCHED_ERR_ARG;
+  }
 
   try {
     const int32_t N = n_gpus, G = n_videos;

@@ -1,8 +1,10 @@
 """GPU parity of the log-sum-exp output, the merge of partial results and cross-attention against the CPU oracle.
 
 Tolerances.  O: the attention bars of tests/gpu_util.py (max-abs 2e-2 and relative L2 1e-2).  lse: computed in fp32 as
-ln 2 * (c*m + log2 l) with l summed in fp32 from unrounded probabilities; its error is a few fp32 ulps of |c*m| (up to
-~60 here) plus the hardware log2's ~1 ulp and the fp32 summation error of l (relative ~1e-6): 1e-4 absolute is asserted.
+ln 2 * (c*m + log2 l), where m is the row's lazily updated reference value and l the fp32 sum of the probabilities as
+rounded to bf16 for the second contraction.  Every rounded term is within 2^-8 relative of its exact value and all are
+positive, so lse is within ln(1 + 2^-8) = 3.9e-3 of the exact value (LSE_TOL below, which is also the contract stated
+in include/dit_attn.h); the fp32 arithmetic around it adds ~1e-5.
 Merged O: the parts are bf16 (2^-9 relative each) and the result is rounded once more, so the same attention bars apply.
 """
 import os
@@ -54,7 +56,7 @@ def _fwd_lse(ctx, w, kernel=None):
     return out, lse
 
 
-@pytest.mark.parametrize("head_dim,kernel", [(64, None), (128, None), (128, da.KERNEL_PINGPONG), (128, da.KERNEL_WIDE), (64, da.KERNEL_WIDE)])
+@pytest.mark.parametrize("head_dim,kernel", [(64, None), (128, None), (128, da.KERNEL_PINGPONG), (64, da.KERNEL_PINGPONG)])
 def test_lse_matches_oracle(ctx, head_dim, kernel):
     w = make_custom([300, 1, 129, 64, 777], 3, head_dim, seed=41)
     out, lse = _fwd_lse(ctx, w, kernel)

@@ -70,20 +70,22 @@ def test_tiny_image_full_oracle(runner):
 
 # ------------------------------------------------------------------ the four large configurations, sampled rows
 
-LARGE = [("t2i_batch", 600), ("t2v_single", 400), ("mixed_varlen", 700), ("sp_shard", 320)]
+# (name, kernel): None = the kernel the library picks for the pack (the benchmark's launch configuration); the second
+# sp_shard entry forces the 128-row kernel, so that its tail path (76112 = 1189 * 64 + 16) is checked at full length too.
+LARGE = [("t2i_batch", None), ("t2v_single", None), ("mixed_varlen", None), ("sp_shard", None), ("sp_shard", "KERNEL_128")]
 
 
-@pytest.mark.parametrize("name,max_rows", LARGE, ids=[n for n, _ in LARGE])
-def test_full_size_configs_sampled_rows(runner, name, max_rows):
-    """Full-size call in the benchmark's launch configuration; the oracle checks a stratified row sample
-    (every sampled row uses all keys of its sequence, so each checked row is exact)."""
+@pytest.mark.parametrize("name,kernel", LARGE, ids=[n + ("" if k is None else "-" + k) for n, k in LARGE])
+def test_full_size_configs_sampled_rows(runner, name, kernel):
+    """Full-size call in the benchmark's launch configuration; the oracle checks a stratified row sample: one row in
+    every 64-row block of every sequence (so every wavefront of every query tile is hit) plus the rows around the
+    sequence ends and tile boundaries, on all heads.  Every sampled row uses all keys of its sequence, so each checked
+    row is exact."""
     _say(f"config {name}: generating")
     w = make_workload(name)
-    if os.environ.get("DIT_ORACLE_FULL") == "1":
-        max_rows = None
-    rows = sample_rows(w.cu_seqlens, seed=w.seed, block=64, max_rows=max_rows)
+    rows = sample_rows(w.cu_seqlens, seed=w.seed, block=64)
     _say(f"config {name}: T={w.total_tokens} H={w.n_heads} rows checked={len(rows)}; running GPU")
-    got = runner.run(w)
+    got = runner.run(w, kernel=None if kernel is None else getattr(da, kernel))
     _say(f"config {name}: running oracle on {len(rows)} rows")
     ref = orc.attention_varlen_rows(w.q, w.k, w.v, w.cu_seqlens, w.scale, rows)
     max_abs, rel = assert_parity(got[rows], ref, name)
@@ -102,6 +104,41 @@ def test_full_size_configs_sampled_rows(runner, name, max_rows):
         if e > s:
             lo, hi = vf[s:e].min(axis=0), vf[s:e].max(axis=0)
             assert np.all(gf[s:e] >= lo[None] - 1e-6) and np.all(gf[s:e] <= hi[None] + 1e-6)
+
+
+def _bf16_ulp(x):
+    """Spacing of bf16 values at |x| (8 significant bits): 2^(floor(log2 |x|) - 7)."""
+    ax = np.maximum(np.abs(x), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(ax)) - 7)
+
+
+def test_t2i_batch_every_output_against_the_oracle(runner):
+    """Configuration 2 (four batched 1024x1024 image requests, per-head value scale) against the oracle on EVERY
+    output.  Its outputs reach |O| = 4..10, where half a bf16 output ulp is already 1.6e-2 (|O| >= 4) and 3.1e-2
+    (|O| >= 8), so the max-abs bar of 2e-2 cannot hold for a bf16 result with |O| >= 8 however it is computed.
+    Asserted: relative L2 <= 1e-2 over everything and per sequence; max-abs <= 2e-2 on every element with |ref| < 8;
+    for the remaining elements (counted, a handful) the error is within output rounding, half a bf16 ulp of the
+    reference plus the 2e-3 that the fp32 arithmetic before the rounding may contribute."""
+    w = make_workload("t2i_batch")
+    _say(f"t2i_batch: T={w.total_tokens} H={w.n_heads}; running GPU")
+    got = widen(runner.run(w))
+    _say("t2i_batch: full oracle (0.93 TFLOP fp64)")
+    ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale)
+    assert np.all(np.isfinite(got))
+    err = np.abs(got - ref)
+    max_abs, rel = errors(got, ref)
+    big = np.abs(ref) >= 8.0
+    _say(f"t2i_batch: rel_l2={rel:.3e} max_abs={max_abs:.3e} max|ref|={np.max(np.abs(ref)):.2f} "
+         f"elements with |ref|>=8: {int(big.sum())}, of them over 2e-2: {int((err[big] > MAX_ABS_TOL).sum())}, "
+         f"elements over 1.8e-2: {int((err > 1.8e-2).sum())}")
+    assert rel <= REL_L2_TOL
+    cu = w.cu_seqlens
+    for i in range(len(cu) - 1):
+        s, e = int(cu[i]), int(cu[i + 1])
+        assert errors(got[s:e], ref[s:e])[1] <= REL_L2_TOL, f"sequence {i}"
+    assert np.max(err[~big], initial=0.0) <= MAX_ABS_TOL
+    assert int(big.sum()) <= 64, "the exception must stay a handful of elements"
+    assert np.all(err[big] <= 0.5 * _bf16_ulp(ref[big]) + 2e-3)
 
 
 def test_tensors_beyond_four_gib(runner):
@@ -207,20 +244,6 @@ def test_both_kernels_give_the_same_bits(runner):
     assert_parity(full[rows], ref, "ping-pong kernel, head_dim 64")
 
 
-@pytest.mark.parametrize("head_dim", [64, 128])
-def test_wide_kernel_gives_the_same_bits(runner, head_dim):
-    """The 64-rows-per-wavefront kernel against the ping-pong kernel on the same 256-row work-list: ragged tiles, a
-    one-tile and a two-tile sequence, lengths around the tile and item sizes, an empty sequence, an odd and an even
-    number of tiles; and against the oracle."""
-    w = make_custom([1500, 64, 128, 1, 333, 2049, 63, 65, 0, 127, 129, 255, 257, 2], 3, head_dim, seed=31)
-    a = runner.run(w, kernel=da.KERNEL_PINGPONG)
-    b = runner.run(w, kernel=da.KERNEL_WIDE)
-    assert np.array_equal(a, b)
-    assert np.array_equal(runner.run(w, scale=-0.3, kernel=da.KERNEL_WIDE), runner.run(w, scale=-0.3, kernel=da.KERNEL_PINGPONG))
-    ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale)
-    assert_parity(b, ref, f"wide kernel, head_dim {head_dim}")
-
-
 def test_launch_clock_sample(runner):
     """The clock sample of the last launch: a plausible shader clock (MI355X runs at 2.4 GHz at most) and a duration."""
     w = make_custom([2048], 8, 128, seed=33)
@@ -230,31 +253,8 @@ def test_launch_clock_sample(runner):
     assert 0.0 < ms < 1000.0, ms
     # 8 x 8 = 64 items of 256 rows: fewer than compute units, so the 128-row kernel ran; a forced kernel is reported too
     assert da.dit_attn_last_launch_kernel(runner.ctx) == da.KERNEL_128
-    runner.run(w, kernel=da.KERNEL_WIDE)
-    assert da.dit_attn_last_launch_kernel(runner.ctx) == da.KERNEL_WIDE
-    runner.run(w, scale=-0.5, kernel=da.KERNEL_WIDE)
+    runner.run(w, kernel=da.KERNEL_PINGPONG)
     assert da.dit_attn_last_launch_kernel(runner.ctx) == da.KERNEL_PINGPONG
-
-
-def test_mfma_ceiling_measurement(runner):
-    """The register-only MFMA stream: between half of the nominal bf16 peak and the peak, at a plausible clock, and
-    consistent with that clock (256 CUs x 4 SIMDs x 1024 flop per cycle); every mix with extra work beside the MFMAs
-    is slower than the MFMAs alone and still above a third of the peak; bad arguments are refused."""
-    _say("mfma ceiling: 10 warm + 10 timed launches per mix")
-    tf, mhz = da.dit_attn_mfma_ceiling(runner.ctx, da.MIX_MFMA_ONLY, 10, 10)
-    _say(f"mfma ceiling: {tf:.0f} TFLOP/s at {mhz:.0f} MHz")
-    assert 1000.0 < mhz < 2500.0
-    assert 0.5 * 2516.6 < tf < 1.01 * 2516.6
-    at_clock = 256 * 4 * 1024 * mhz * 1e6 / 1e12
-    assert 0.9 * at_clock < tf < 1.02 * at_clock
-    for mix in (da.MIX_PINGPONG, da.MIX_LDS, da.MIX_VALU, da.MIX_64ROW, da.MIX_WIDE):
-        t2, m2 = da.dit_attn_mfma_ceiling(runner.ctx, mix, 10, 10)
-        _say(f"mix {mix}: {t2:.0f} TFLOP/s at {m2:.0f} MHz")
-        assert 2516.6 / 3 < t2 < tf and 1000.0 < m2 < 2500.0
-    for mix, warm, timed in ((0, -1, 1), (0, 0, 0), (0, 1001, 1), (0, 0, 1001), (-1, 1, 1), (6, 1, 1)):
-        with pytest.raises(da.DitAttnError) as e:
-            da.dit_attn_mfma_ceiling(runner.ctx, mix, warm, timed)
-        assert e.value.code == -11
 
 
 def test_head_subset_equals_heads_of_wider_run(runner):
@@ -331,10 +331,10 @@ def test_lazy_reference_staircase(runner):
         kf[:, :, 0] = np.tile(np.repeat(level, 64), reps)[:, None]
         w.q, w.k = f32_to_bf16_bits(qf), f32_to_bf16_bits(kf)
         ref = orc.attention_varlen(w.q, w.k, w.v, w.cu_seqlens, w.scale)
-        outs = [runner.run(w, kernel=kern) for kern in (da.KERNEL_128, da.KERNEL_PINGPONG, da.KERNEL_WIDE)]
+        outs = [runner.run(w, kernel=kern) for kern in (da.KERNEL_128, da.KERNEL_PINGPONG)]
         for got in outs:
             assert_parity(got, ref, "staircase logits")
-        assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[1], outs[2])
+        assert np.array_equal(outs[0], outs[1])
 
 
 # ------------------------------------------------------------------ call mechanics
@@ -400,6 +400,35 @@ def test_graph_capture_and_replay(runner, lens, heads):
     rows = sample_rows(w.cu_seqlens, seed=5, block=16, max_rows=64)
     ref = orc.attention_varlen_rows(w.q, w.k, w.v, w.cu_seqlens, w.scale, rows)
     assert_parity(to_bits(out)[rows], ref, "graph replay")
+
+
+def test_captured_pack_survives_plan_cache_eviction(runner):
+    """A captured launch keeps reading its pack's device work-list on every replay, so that pack is pinned in the plan
+    cache: after more distinct packs than the cache holds have gone through the context, a replay still reproduces the
+    eager bits.  A call under capture for a pack the context has never seen is refused (it would have to allocate and
+    copy), and the capture can go on without it."""
+    w = make_custom([500, 130], 2, 128, seed=40)
+    q, k, v = to_dev(w.q), to_dev(w.k), to_dev(w.v)
+    stream = lambda: torch.cuda.current_stream().cuda_stream
+    eager = torch.empty_like(q)
+    da.dit_attn_varlen_fwd(runner.ctx, q, k, v, w.cu_seqlens, 2, 128, w.scale, eager, stream())
+    torch.cuda.synchronize()
+    out = torch.zeros_like(q)
+    unseen = np.array([0, 499, 630], dtype=np.int32)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        with pytest.raises(da.DitAttnError) as ei:
+            da.dit_attn_varlen_fwd(runner.ctx, q, k, v, unseen, 2, 128, w.scale, out, stream())
+        assert ei.value.code == -12
+        da.dit_attn_varlen_fwd(runner.ctx, q, k, v, w.cu_seqlens, 2, 128, w.scale, out, stream())
+    torch.cuda.synchronize()
+    for i in range(40):  # more distinct packs than the cache holds: every unpinned plan is evicted at least once
+        runner.run(make_custom([70 + i, 9], 1, 64, seed=41))
+    out.zero_()
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), eager.view(torch.int16))
 
 
 def test_empty_inputs_launch_nothing(runner):

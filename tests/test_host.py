@@ -28,7 +28,6 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert {"dit_attn_create", "dit_attn_varlen_fwd", "dit_attn_destroy", "dit_attn_last_error",
             "dit_attn_plan", "dit_attn_version", "dit_attn_varlen_fwd_lse", "dit_attn_cross_varlen_fwd", "dit_attn_merge",
             "dit_attn_sp_pack_heads", "dit_attn_sp_unpack_heads", "dit_attn_set_kernel", "dit_attn_last_launch_clock", "dit_attn_last_launch_kernel",
-            "dit_attn_mfma_ceiling",
             "dit_sched_plan_round", "dit_sched_laxity"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -134,3 +133,18 @@ def test_kernel_choice_by_items_per_compute_unit():
     assert block_m([20506], 24) == 256
     assert block_m([4352] * 4, 24) == 256
     assert block_m([1024], 8) == 128
+
+
+def test_plan_cache_evicts_least_recently_used_unpinned_pack():
+    """A pack whose launch was recorded into a HIP graph is pinned and never evicted; among the others the least
+    recently used one goes; when all are pinned nothing is evicted (the cache grows)."""
+    v = da.dit_attn_plan_cache_victim
+    assert v([5, 3, 9, 4], [0, 0, 0, 0]) == 1
+    assert v([5, 3, 9, 4], [0, 1, 0, 0]) == 3
+    assert v([5, 3, 9, 4], [0, 1, 0, 1]) == 0
+    assert v([5, 3, 9, 4], [1, 1, 0, 1]) == 2
+    assert v([5, 3, 9, 4], [1, 1, 1, 1]) == -1
+    assert v([], []) == -1
+    assert v([7], [0]) == 0
+    # ties: the first of equal use counts
+    assert v([2, 2, 2], [1, 0, 0]) == 1

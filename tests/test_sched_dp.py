@@ -162,6 +162,12 @@ def test_cpp_laxity_and_errors():
     with pytest.raises(da.DitAttnError) as e:
         da.dit_sched_plan_round(2, [[(2, 0, 1.0, False)], [(1, 0, 1.0, False)]], [], 0.0, T_IMG)  # no hold, does not fit
     assert e.value.code == -3
+    with pytest.raises(da.DitAttnError) as e:
+        da.dit_sched_plan_round(4, [[(0, 0, 0.0, True), (2, 0b0111, 1.0, False)]], [], 0.0, T_IMG)  # mask names 3 GPUs, gpus says 2
+    assert e.value.code == -2
+    with pytest.raises(da.DitAttnError) as e:
+        da.dit_sched_plan_round(4, [[da.SchedCandidate(1, 0, 1.0, 0, 7)]], [], 0.0, T_IMG)          # reserved must be 0
+    assert e.value.code == -2
     r = da.dit_sched_plan_round(8, [], [], 0.0, T_IMG)                           # nothing to do
     assert r["recoverable"] == 0 and r["video_gpus"] == 0 and r["n_batches"] == 0
 
