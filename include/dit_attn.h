@@ -102,6 +102,24 @@ int dit_attn_varlen_fwd(dit_attn_ctx* ctx,
                         void* out, void* stream);
 
 /*
+ * For callers that cannot allocate device memory: code being recorded into a HIP graph that meets a pack for the first
+ * time, tight serving loops, harnesses that forbid hipMalloc.  The same operation as dit_attn_varlen_fwd, same
+ * arguments, same result bit for bit, but the call allocates nothing and copies nothing: the work-list is written by a
+ * small kernel on `stream` (the sequence boundaries travel as its argument) into a fixed device array of the library
+ * (256 KB + 256 B per GPU, held until the process ends), which also holds the kernels' work counters.
+ * Limits: n_seqs <= 64 and at most 16384 work items per pack (an item is 256 query rows of one head, 128 for packs that
+ * the 128-row kernel runs; the five benchmark configurations need 32 to 4632); beyond them DIT_ATTN_ERR_LIMIT, `out`
+ * untouched.  No split-KV, no plan cache, dit_attn_last_launch_clock is not updated.
+ * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, contexts or threads) race;
+ * calls on one stream are ordered and safe.  Other return codes as dit_attn_varlen_fwd.
+ */
+int dit_attn_varlen_fwd_noalloc(dit_attn_ctx* ctx,
+                                const void* q, const void* k, const void* v,
+                                const int32_t* cu_seqlens, int32_t n_seqs,
+                                int32_t n_heads, int32_t head_dim, float scale,
+                                void* out, void* stream);
+
+/*
  * Destroy a context and free its device memory (host call).  The caller must
  * have synchronised every stream the context was used on.  NULL is a no-op.
  */

@@ -23,6 +23,7 @@ __all__ = [
     "dit_attn_version",
     "dit_attn_create",
     "dit_attn_varlen_fwd",
+    "dit_attn_varlen_fwd_noalloc",
     "dit_attn_varlen_fwd_lse",
     "dit_attn_cross_varlen_fwd",
     "dit_attn_merge",
@@ -98,6 +99,8 @@ def load_library() -> ctypes.CDLL:
     lib.dit_attn_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int]
     lib.dit_attn_varlen_fwd.restype = ctypes.c_int
     lib.dit_attn_varlen_fwd.argtypes = [vp, vp, vp, vp, i32p, i32, i32, i32, ctypes.c_float, vp, vp]
+    lib.dit_attn_varlen_fwd_noalloc.restype = ctypes.c_int
+    lib.dit_attn_varlen_fwd_noalloc.argtypes = [vp, vp, vp, vp, i32p, i32, i32, i32, ctypes.c_float, vp, vp]
     lib.dit_attn_destroy.restype = None
     lib.dit_attn_destroy.argtypes = [vp]
     lib.dit_attn_varlen_fwd_lse.restype = ctypes.c_int
@@ -219,6 +222,21 @@ def dit_attn_varlen_fwd(ctx, q, k, v, cu_seqlens, n_heads: int, head_dim: int, s
                                  ctypes.c_void_p(_ptr(v)), cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
                                  int(n_seqs), int(n_heads), int(head_dim), float(scale),
                                  ctypes.c_void_p(_ptr(out)), ctypes.c_void_p(_ptr(stream)))
+    if rc != 0:
+        raise DitAttnError(rc, dit_attn_last_error(ctx))
+
+
+def dit_attn_varlen_fwd_noalloc(ctx, q, k, v, cu_seqlens, n_heads: int, head_dim: int, scale: float, out, stream=None,
+                                n_seqs: int | None = None) -> None:
+    """dit_attn_varlen_fwd for callers that cannot allocate: same arguments and result, fixed limits; see include/dit_attn.h."""
+    lib = load_library()
+    cu = _cu_array(cu_seqlens)
+    if n_seqs is None:
+        n_seqs = len(cu) - 1
+    rc = lib.dit_attn_varlen_fwd_noalloc(ctypes.c_void_p(ctx), ctypes.c_void_p(_ptr(q)), ctypes.c_void_p(_ptr(k)),
+                                         ctypes.c_void_p(_ptr(v)), cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                         int(n_seqs), int(n_heads), int(head_dim), float(scale),
+                                         ctypes.c_void_p(_ptr(out)), ctypes.c_void_p(_ptr(stream)))
     if rc != 0:
         raise DitAttnError(rc, dit_attn_last_error(ctx))
 

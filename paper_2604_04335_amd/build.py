@@ -9,7 +9,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libdit_attn.so")
-SOURCES = ["api.cpp", "plan.cpp", "sched_dp.cpp", "attn_fwd.hip", "merge.hip", "sp_layout.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "sched_dp.cpp", "attn_fwd.hip", "merge.hip", "sp_layout.hip", "noalloc.hip"]
 # bench.py's measurement aid (matrix-pipe ceiling loops); a library of its own that the attention library never loads
 PROBE_LIB_PATH = os.path.join(PKG_DIR, "libdit_probe.so")
 PROBE_SOURCES = ["probe/mfma_ceiling.hip"]

@@ -16,6 +16,7 @@
 
 #include "attn_fwd.h"
 #include "merge.h"
+#include "noalloc.h"
 #include "plan.h"
 #include "sp_layout.h"
 
@@ -150,6 +151,9 @@ int dit_attn_create(dit_attn_ctx** out_ctx, int device_id) {
   e = guard.enter(device_id);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->sync), 8 * sizeof(uint32_t));
   if (e == hipSuccess) e = hipMemset(ctx->sync, 0, 8 * sizeof(uint32_t));
+  // Kernel code resident and LDS limits set before the first launch; this device's fixed scratch resolved.
+  if (e == hipSuccess) e = dit::attn_fwd_prepare();
+  if (e == hipSuccess) e = dit::noalloc_init(device_id);
   if (e != hipSuccess) {
     (void)hipGetLastError();
     g_create_error = std::string("context set-up: ") + hipGetErrorString(e);
@@ -469,6 +473,54 @@ int dit_attn_cross_varlen_fwd(dit_attn_ctx* ctx, const void* q, const void* k, c
                               void* out, float* lse, void* stream) {
   if (ctx && !cu_seqlens_k) return fail(ctx, DIT_ATTN_ERR_NULL, "cu_seqlens_k is NULL");
   return forward(ctx, q, k, v, cu_seqlens_q, cu_seqlens_k, n_seqs, n_heads, head_dim, scale, out, lse, stream);
+}
+
+int dit_attn_varlen_fwd_noalloc(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                                int32_t n_seqs, int32_t n_heads, int32_t head_dim, float scale, void* out, void* stream) {
+  if (!ctx) return DIT_ATTN_ERR_NULL;
+  ctx->error.clear();
+  std::string msg;
+  const int rc = check_shape_args(cu_seqlens, n_seqs, n_heads, head_dim, msg);
+  if (rc != DIT_ATTN_OK) return fail(ctx, rc, msg);
+  if (!std::isfinite(scale)) return fail(ctx, DIT_ATTN_ERR_SCALE, "scale must be finite");
+  const int64_t total = n_seqs > 0 ? cu_seqlens[n_seqs] : 0;
+  if (n_seqs == 0 || total == 0) return DIT_ATTN_OK;
+  if (!q || !k || !v || !out) return fail(ctx, DIT_ATTN_ERR_NULL, "q, k, v and out must be non-NULL");
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) |
+                         reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(out);
+  if (bits & 15u) return fail(ctx, DIT_ATTN_ERR_ALIGN, "q, k, v and out must be 16-byte aligned");
+  if (n_seqs > dit::kNoAllocMaxSeqs)
+    return fail(ctx, DIT_ATTN_ERR_LIMIT, "dit_attn_varlen_fwd_noalloc takes at most " + std::to_string(dit::kNoAllocMaxSeqs) + " sequences per pack");
+  const dit::AttnKernel kernel = ctx->force_kernel >= 0 ? static_cast<dit::AttnKernel>(ctx->force_kernel)
+                                                        : dit::attn_fwd_select(cu_seqlens, nullptr, n_seqs, n_heads, ctx->n_cus);
+  const int32_t bm = dit::attn_fwd_block_m(kernel);
+  int64_t n_items = 0;
+  for (int32_t i = 0; i < n_seqs; ++i) n_items += static_cast<int64_t>((cu_seqlens[i + 1] - cu_seqlens[i] + bm - 1) / bm) * n_heads;
+  if (n_items > dit::kNoAllocMaxItems)
+    return fail(ctx, DIT_ATTN_ERR_LIMIT, "dit_attn_varlen_fwd_noalloc takes at most " + std::to_string(dit::kNoAllocMaxItems) +
+                                             " work items per pack, this pack has " + std::to_string(n_items));
+  DeviceGuard guard;
+  hipError_t e = guard.enter(ctx->device);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  dit::AttnParams p{};
+  const dit::WorkItem* items = nullptr;
+  e = dit::noalloc_plan_launch(ctx->device, cu_seqlens, n_seqs, n_heads, bm, static_cast<uint32_t>(n_items), s, &items, &p.sync);
+  if (e != hipSuccess) return fail_hip(ctx, e, "work-list kernel launch");
+  p.q = q;
+  p.k = k;
+  p.v = v;
+  p.out = out;
+  p.items = items;
+  p.n_items = static_cast<uint32_t>(n_items);
+  p.n_heads = n_heads;
+  p.c_log2 = std::fabs(scale) * 1.44269504088896340736f;
+  p.negate = scale < 0.f ? 1 : 0;
+  const int64_t max_grid = static_cast<int64_t>(ctx->n_cus) * dit::attn_fwd_wgs_per_cu(kernel);
+  e = dit::attn_fwd_launch(p, kernel, head_dim, static_cast<int>(n_items < max_grid ? n_items : max_grid), s);
+  if (e != hipSuccess) return fail_hip(ctx, e, "kernel launch");
+  ctx->last_kernel = static_cast<int>(kernel);
+  return DIT_ATTN_OK;
 }
 
 static int sp_layout(dit_attn_ctx* ctx, bool pack, const void* src, void* dst, int64_t n_rows, int32_t n_heads,

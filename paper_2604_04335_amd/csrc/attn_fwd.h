@@ -44,6 +44,10 @@ AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_
 int attn_fwd_block_m(AttnKernel kernel);
 int attn_fwd_wgs_per_cu(AttnKernel kernel);
 
+// Load the code of every attention kernel on the current device and set its LDS limit (a launch would otherwise do both
+// the first time, which allocates; dit_attn_create calls this so that no later launch has to).
+hipError_t attn_fwd_prepare();
+
 // Enqueue the forward kernel with `grid` persistent workgroups.
 hipError_t attn_fwd_launch(const AttnParams& p, AttnKernel kernel, int head_dim, int grid, hipStream_t stream);
 

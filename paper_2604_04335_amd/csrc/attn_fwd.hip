@@ -259,8 +259,9 @@ attn_fwd_pp_kernel(AttnParams p) {
   if (tid == 0) finish_workgroup(p);
 }
 
+// The LDS limit of a kernel is set once per device (its first use there also loads the kernel's code).
 template <class T, void (*KERNEL)(AttnParams)>
-static hipError_t launch_t(const AttnParams& p, int grid, hipStream_t stream) {
+static hipError_t prepare_t() {
   static bool attr_set[16] = {};
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -270,8 +271,23 @@ static hipError_t launch_t(const AttnParams& p, int grid, hipStream_t stream) {
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 16) attr_set[dev] = true;
   }
+  return hipSuccess;
+}
+
+template <class T, void (*KERNEL)(AttnParams)>
+static hipError_t launch_t(const AttnParams& p, int grid, hipStream_t stream) {
+  const hipError_t e = prepare_t<T, KERNEL>();
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(KERNEL, dim3(grid), dim3(T::NT), T::LDS_BYTES, stream, p);
   return hipGetLastError();
+}
+
+hipError_t attn_fwd_prepare() {
+  hipError_t e = prepare_t<Tile<128, 8, 64, 2>, attn_fwd_pp_kernel<Tile<128, 8, 64, 2>>>();
+  if (e == hipSuccess) e = prepare_t<Tile<64, 8, 64, 2>, attn_fwd_pp_kernel<Tile<64, 8, 64, 2>>>();
+  if (e == hipSuccess) e = prepare_t<Tile<128, 4, 64>, attn_fwd_kernel<Tile<128, 4, 64>>>();
+  if (e == hipSuccess) e = prepare_t<Tile<64, 4, 64>, attn_fwd_kernel<Tile<64, 4, 64>>>();
+  return e;
 }
 
 int attn_fwd_block_m(AttnKernel kernel) { return kernel == AttnKernel::kIndependent128 ? 128 : 256; }
