@@ -335,6 +335,8 @@ def main():
     ap.add_argument("--op", default="attn", choices=["attn", "merge", "cross", "layout", "sched"],
                     help="attn: the denoising-step self-attention (the headline line); merge / cross: one line for the "
                          "partial-result merge kernel (HBM bound) or for cross-attention against text keys")
+    ap.add_argument("--kernel", default="auto", choices=["auto", "128", "pingpong"],
+                    help="force one of the library's kernels (dit_attn_set_kernel); auto: chosen per pack")
     ap.add_argument("--zero-operands", action="store_true",
                     help="power check, not the metric: time the same launch on all-zero Q, K, V (the line says so in `data`)")
     ap.add_argument("--no-second", action="store_true",
@@ -371,6 +373,7 @@ def main():
         return
     ctx = da.dit_attn_create(0)
     da.dit_attn_set_split_kv(ctx, args.split_kv)
+    da.dit_attn_set_kernel(ctx, {"auto": da.KERNEL_AUTO, "128": da.KERNEL_128, "pingpong": da.KERNEL_PINGPONG}[args.kernel])
     if args.op != "attn":
         print(json.dumps(bench_other(da, torch, ctx, args)), flush=True)
         da.dit_attn_destroy(ctx)

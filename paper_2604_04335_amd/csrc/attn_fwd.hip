@@ -100,11 +100,15 @@ attn_fwd_kernel(AttnParams p) {
 // of an item (p = 0 after the first barrier):
 //     group 0:  QK(P0) at p=0,  softmax(Pt) at p=2t+1,  PV(Pt)+QK(Pt+1) at p=2t+2
 //     group 1:  idle   at p=0,  QK(P0) at p=1, softmax(Pt) at p=2t+2, PV(Pt)+QK(Pt+1) at p=2t+3
-// K(Pt+1) and V(Pt) are therefore read in phases 2t+2 and 2t+3 only; their buffers (parity of the pair index) are
-// refilled with K(Pt+3) / V(Pt+2) from phase 2t+4 on.  {K(Pt+2), V(Pt+1)} is issued at the start of phase 2t+2 by
-// group 1, which is then in its vector phase, for both groups (a wavefront in its matrix phase is the critical path
-// and issues nothing but MFMAs and operand reads), and awaited by group 1 at the end of phase 2t+3, before the barrier
-// that lets group 0 read it.  A sequence with an odd number of tiles ends in a pair of one tile; the QK MFMAs of the
+// K(Pt+1) and V(Pt) are therefore read in phases 2t+2 and 2t+3 only; their buffers (parity of the pair index) can be
+// refilled with K(Pt+3) / V(Pt+2) from phase 2t+4 on.  Loads are issued by wavefronts in their vector phase only (a
+// wavefront in its matrix phase is the critical path and issues nothing but MFMAs and operand reads; a direct load
+// holds its wavefront for ~64 cycles), each for its own rows and those of the wavefront four away, and the two groups
+// share the issue: group 1 issues V(Pt+1) at the start of phase 2t+2 and awaits it at the end of phase 2t+3, before the
+// barrier that lets group 0 read it; group 0 issues K(Pt+1) at the start of phase 2t+1 (its buffer was last read in
+// phase 2t-1) and awaits it at the end of the same phase, behind its two softmaxes (about 0.8 us later: K comes from
+// L2 or the memory-side cache, whose latency that covers).  All of it in group 1 made that group's vector phase the
+// longest phase by ~500 cycles.  A sequence with an odd number of tiles ends in a pair of one tile; the QK MFMAs of the
 // missing tile run on whatever its buffer half holds and their scores are never read.
 // ---------------------------------------------------------------------------------------------
 template <class T>
@@ -154,31 +158,44 @@ attn_fwd_pp_kernel(AttnParams p) {
       load_v(2 * t, lrow, vvoff, wave);
       load_v(2 * t + 1, lrow, vvoff, wave);
     };
-    // Inside the pair loop group 1 issues the loads of both groups (its own rows and those of wave-4).  While all four
-    // tiles are whole interior tiles (every tile but the last of a sequence) their rows form one run of 2 * LPT load
-    // rounds per tensor, GROUP rows apart: the addresses come from one running pointer and the load issue, which sits
-    // on the critical path of this group's vector phase, carries no per-tile tests or multiplications.
-    const uint32_t d4 = (uint32_t)(4 * T::RPI) * (uint32_t)row_stride_b;
+    // Inside the pair loop the group that is in its vector phase issues loads for both groups (its own rows and those
+    // of the wavefront four away).  While the tiles are whole interior tiles (every tile but the last of a sequence)
+    // their rows form one run of 2 * LPT load rounds, GROUP rows apart: the addresses come from one running pointer
+    // and the load issue, which sits on the critical path of the vector phase, carries no per-tile tests or
+    // multiplications.
+    const int other = group == 1 ? -4 : 4;  // the wavefront whose rows this one also loads
+    const uint32_t d4 = (uint32_t)(other * T::RPI) * (uint32_t)row_stride_b;
     const int64_t round_b = (int64_t)T::GROUP * row_stride_b;
-    auto load_pair_all = [&](int t) {
-      if (2 * t + 3 < nt - 1) {
-        const char* kp = X.kbase + (int64_t)(2 * t + 2) * T::BN * row_stride_b;
-        const char* vp = X.vbase + (int64_t)(2 * t) * T::BN * row_stride_b;
-        const uint32_t lk = (uint32_t)(uintptr_t)smem + T::K_OFF + ((t + 1) & 1) * T::BUF_B + (uint32_t)L.wave * 1024u;
-        const uint32_t lv = (uint32_t)(uintptr_t)smem + T::V_OFF + (t & 1) * T::BUF_B + (uint32_t)L.wave * 1024u;
+    auto load_k_pair_all = [&](int tp) {  // K tiles 2tp, 2tp+1 -> K buffer tp&1
+      if (2 * tp + 1 < nt - 1) {
+        const char* kp = X.kbase + (int64_t)(2 * tp) * T::BN * row_stride_b;
+        const uint32_t lk = (uint32_t)(uintptr_t)smem + T::K_OFF + (tp & 1) * T::BUF_B + (uint32_t)L.wave * 1024u;
 #pragma unroll
         for (int j = 0; j < 2 * T::LPT; ++j) {
           lds_dma_16(kp + j * round_b, L.kvoff, lk + j * T::NWAVES * 1024);
-          lds_dma_16(kp + j * round_b, L.kvoff - d4, lk + j * T::NWAVES * 1024 - 4096);
+          lds_dma_16(kp + j * round_b, L.kvoff + d4, lk + j * T::NWAVES * 1024 + other * 1024);
         }
+      } else {
+        load_k(2 * tp, L.lrow, L.kvoff, L.wave);
+        load_k(2 * tp + 1, L.lrow, L.kvoff, L.wave);
+        load_k(2 * tp, L.lrow + other * T::RPI, L.kvoff + d4, L.wave + other);
+        load_k(2 * tp + 1, L.lrow + other * T::RPI, L.kvoff + d4, L.wave + other);
+      }
+    };
+    auto load_v_pair_all = [&](int tp) {  // V tiles 2tp, 2tp+1 -> V buffer tp&1
+      if (2 * tp + 1 < nt - 1) {
+        const char* vp = X.vbase + (int64_t)(2 * tp) * T::BN * row_stride_b;
+        const uint32_t lv = (uint32_t)(uintptr_t)smem + T::V_OFF + (tp & 1) * T::BUF_B + (uint32_t)L.wave * 1024u;
 #pragma unroll
         for (int j = 0; j < 2 * T::LPT; ++j) {
           lds_dma_16(vp + j * round_b, L.vvoff, lv + j * T::NWAVES * 1024);
-          lds_dma_16(vp + j * round_b, L.vvoff - d4, lv + j * T::NWAVES * 1024 - 4096);
+          lds_dma_16(vp + j * round_b, L.vvoff + d4, lv + j * T::NWAVES * 1024 + other * 1024);
         }
       } else {
-        load_pair(t, L.lrow, L.kvoff, L.vvoff, L.wave);
-        load_pair(t, L.lrow - 4 * T::RPI, L.kvoff - d4, L.vvoff - d4, L.wave - 4);
+        load_v(2 * tp, L.lrow, L.vvoff, L.wave);
+        load_v(2 * tp + 1, L.lrow, L.vvoff, L.wave);
+        load_v(2 * tp, L.lrow + other * T::RPI, L.vvoff + d4, L.wave + other);
+        load_v(2 * tp + 1, L.lrow + other * T::RPI, L.vvoff + d4, L.wave + other);
       }
     };
     load_k(0, L.lrow, L.kvoff, L.wave);
@@ -214,9 +231,11 @@ attn_fwd_pp_kernel(AttnParams p) {
     for (int t = 0; t + 1 < npairs; ++t) {
       // ---- vector phase: softmax of both tiles of pair t (whole tiles)
       if (t + 2 == npairs && tid == 0) s_item[par] = take_item(p);
-      if (group == 1) load_pair_all(t + 1);
+      if (group == 1) load_v_pair_all(t + 1);            // read from phase 2t+4 on
+      if (group == 0 && t >= 1) load_k_pair_all(t + 1);  // read from the next phase on (K(P1) came with the prologue)
       tile_softmax<T, false, true>(s[0], L.hh, TailRows{0, T::BN}, c, pb[0], o, m_ref, l_run);
       grown = tile_softmax<T, false, true, true>(s[1], L.hh, TailRows{0, T::BN}, c, pb[1], o, m_ref, l_run, &alpha1);
+      if (group == 0) wait_loads();
       wg_barrier();
       // ---- matrix phase: PV(Pt), QK(Pt+1)
       __builtin_amdgcn_s_setprio(1);
