@@ -430,7 +430,7 @@ int forward(dit_attn_ctx* ctx, const void* q, const void* k, const void* v, cons
   p.sync = ctx->sync;
   p.n_items = n_items;
   p.n_heads = n_heads;
-  p.c_log2 = std::fabs(scale) * 1.44269504088896340736f;
+  p.c_log2 = std::max(std::fabs(scale) * 1.44269504088896340736f, 1e-30f);
   p.negate = scale < 0.f ? 1 : 0;
   e = dit::attn_fwd_launch(p, plan->kernel, head_dim, grid, s);
   if (e != hipSuccess) return fail_hip(ctx, e, "kernel launch");
@@ -514,7 +514,7 @@ int dit_attn_varlen_fwd_noalloc(dit_attn_ctx* ctx, const void* q, const void* k,
   p.items = items;
   p.n_items = static_cast<uint32_t>(n_items);
   p.n_heads = n_heads;
-  p.c_log2 = std::fabs(scale) * 1.44269504088896340736f;
+  p.c_log2 = std::max(std::fabs(scale) * 1.44269504088896340736f, 1e-30f);
   p.negate = scale < 0.f ? 1 : 0;
   const int64_t max_grid = static_cast<int64_t>(ctx->n_cus) * dit::attn_fwd_wgs_per_cu(kernel);
   e = dit::attn_fwd_launch(p, kernel, head_dim, static_cast<int>(n_items < max_grid ? n_items : max_grid), s);

@@ -432,14 +432,18 @@ __device__ __forceinline__ uint64_t tile_softmax(f32x16 (&s)[T::NKB], int hh, Ta
                                                  uint32_t (&pb)[T::NKB][8], f32x16 (&o)[T::NDB], float& m_ref,
                                                  float& l_run, float* alpha_out = nullptr) {
   static_assert(PHASED || !DEFER, "a deferred rescale needs the phased row sums");
+  // Tail mask.  Element i of block kb is key 32 kb + 8 (i / 4) + (i % 4) + 4 hh: the key is dead (not a new key of this
+  // tile) unless lo <= key < hi, tested as one unsigned compare of a compile-time constant against two per-lane
+  // values.  (With the per-lane part folded into the key instead, the compiler keeps all 32 key indices of a lane
+  // in registers across the whole kernel and turns the masking into branches around the exponentials.)
+  const int tail_lo = rows.lo - 4 * hh;
+  const unsigned tail_n = (unsigned)(rows.hi - rows.lo);
+  auto dead = [&](int kb, int i) { return (unsigned)(32 * kb + 8 * (i >> 2) + (i & 3) - tail_lo) >= tail_n; };
   if (TAIL) {
 #pragma unroll
     for (int kb = 0; kb < T::NKB; ++kb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = 32 * kb + 8 * (i >> 2) + 4 * hh + (i & 3);
-        if (key < rows.lo || key >= rows.hi) s[kb][i] = -__builtin_inff();
-      }
+      for (int i = 0; i < 16; ++i) s[kb][i] = dead(kb, i) ? -__builtin_inff() : s[kb][i];
   }
 
   // v_max3_f32 written out, one asm statement per block of 16 scores: through fmaxf the compiler first "quiets"
@@ -501,12 +505,7 @@ __device__ __forceinline__ uint64_t tile_softmax(f32x16 (&s)[T::NKB], int hh, Ta
       for (int i = 8 * g; i < 8 * g + 8; i += 2) {
         float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -mc));
         float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i + 1], c, -mc));
-        if (TAIL) {
-          const int key = 32 * kb + 8 * (i >> 2) + 4 * hh + (i & 3);
-          if (key < rows.lo || key >= rows.hi) p0 = 0.f;
-          if (key + 1 < rows.lo || key + 1 >= rows.hi) p1 = 0.f;
-        }
-        pb[kb][i >> 1] = pack_bf16x2(p0, p1);
+        pb[kb][i >> 1] = pack_bf16x2(p0, p1);  // a dead key: score -inf, c > 0 (AttnParams::c_log2), probability 0
         if constexpr (!PHASED) lsum = add_prob_pair(lsum, pb[kb][i >> 1]);
       }
       SCHED_FENCE();
@@ -665,14 +664,13 @@ struct ItemCtx {
   const char* kbase;
   const char* vbase;
   int qrow;
-  bool row_valid;
+  int row_valid;  // 0 or 1 (an int, so that the struct has no padding bytes to copy around)
 };
 
 template <class T>
-__device__ __forceinline__ ItemCtx<T> begin_item(const AttnParams& p, const Lane<T>& L, uint32_t item_idx,
-                                                 int64_t row_stride_b) {
+__device__ __forceinline__ ItemCtx<T> item_ctx(const AttnParams& p, const Lane<T>& L, const ItemU& it, int64_t row_stride_b) {
   ItemCtx<T> c;
-  c.it = fetch_item(p.items, item_idx);
+  c.it = it;
   c.nt = (c.it.kv_len + T::BN - 1) / T::BN;
   c.head_off = (int64_t)c.it.head * T::D * 2;
   c.kbase = static_cast<const char*>(p.k) + (int64_t)c.it.kv_start * row_stride_b + c.head_off;
@@ -682,6 +680,12 @@ __device__ __forceinline__ ItemCtx<T> begin_item(const AttnParams& p, const Lane
   c.row_valid = c.qrow < c.it.q_rows;
   if (!c.row_valid) c.qrow = c.it.q_rows - 1;
   return c;
+}
+
+template <class T>
+__device__ __forceinline__ ItemCtx<T> begin_item(const AttnParams& p, const Lane<T>& L, uint32_t item_idx,
+                                                 int64_t row_stride_b) {
+  return item_ctx<T>(p, L, fetch_item(p.items, item_idx), row_stride_b);
 }
 
 }  // namespace dit

@@ -25,7 +25,8 @@ struct AttnParams {
                             // replayed from a captured graph, and the host keeps no count).
   uint32_t n_items;
   int32_t n_heads;
-  float c_log2;             // |scale| * log2(e)
+  float c_log2;             // |scale| * log2(e), at least 1e-30: never zero, so that a masked score of -inf times it
+                            // stays -inf (scale 0 then gives every live key the same weight, as it must)
   int32_t negate;           // 1 when scale < 0: the sign of Q is flipped on load
 };
 

@@ -50,7 +50,7 @@ attn_fwd_kernel(AttnParams p) {
     for (int db = 0; db < T::NDB; ++db)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-    float m_ref = -1.0e30f;  // finite, so that (m_ref - m) * 0 is 0 when scale is 0
+    float m_ref = -1.0e30f;  // finite: (m_ref - m) * c stays finite
     float l_run = 0.f;
     f32x16 s[T::NKB];
     uint32_t pb[T::NKB][8];
@@ -210,7 +210,7 @@ attn_fwd_pp_kernel(AttnParams p) {
     for (int db = 0; db < T::NDB; ++db)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-    float m_ref = -1.0e30f;  // finite, so that (m_ref - m) * 0 is 0 when scale is 0
+    float m_ref = -1.0e30f;  // finite: (m_ref - m) * c stays finite
     float l_run = 0.f;
     f32x16 s[2][T::NKB];
     uint32_t pb[2][T::NKB][8];
