@@ -123,9 +123,26 @@ attn_fwd_pp_kernel(AttnParams p) {
   const int tid = threadIdx.x;
   const int64_t row_stride_b = (int64_t)p.n_heads * T::D * 2;
   const float c = p.c_log2;
-  Lane<T> L;
-  L.init(tid, row_stride_b);
-  const int group = L.wave >> 2;
+  // Per-lane constants.  Only the two load offsets stay in registers for the life of the kernel; everything else is
+  // recomputed where an item starts or ends (fresh_lane: some twenty instructions), from a thread index that the
+  // compiler cannot see through.  Kept live instead, they sit in registers that the pair loop needs and are spilled
+  // around it: sixty scratch instructions per wavefront and item, on the one vector-memory path that the item's first
+  // loads and output stores also go through.
+  auto fresh_lane = [&]() {
+    int t = tid;
+    asm volatile("" : "+v"(t));
+    Lane<T> l;
+    l.init(t, row_stride_b);
+    return l;
+  };
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int group = wave >> 2;
+  uint32_t kvoff, vvoff;
+  {
+    const Lane<T> L0 = fresh_lane();
+    kvoff = L0.kvoff;
+    vvoff = L0.vvoff;
+  }
 
   // The index of the next item is requested towards the end of an item, into the slot of the other parity; a barrier
   // between that write and the end of the item makes it visible to every wave before it is read.
@@ -137,26 +154,23 @@ attn_fwd_pp_kernel(AttnParams p) {
     const uint32_t item_idx = __builtin_amdgcn_readfirstlane(s_item[par]);
     if (item_idx >= p.n_items) break;
     par ^= 1;  // the next index goes to s_item[par], see below
-    const ItemCtx<T> X = begin_item<T>(p, L, item_idx, row_stride_b);
+    const ItemCtx<T> X = begin_item<T>(p, fresh_lane(), item_idx, row_stride_b);
     const int kv_len = X.it.kv_len, nt = X.nt;  // nt: 64-key tiles
     const int npairs = (nt + 1) >> 1;
 
     // Tile ti of K / V -> half ti&1 of the buffer of parity (ti>>1)&1, for the rows of wavefront `wave`.
-    auto load_k = [&](int ti, int lrow, uint32_t voff, int wave) {
+    // dw: 0 for this wavefront's own rows, `other` for those of the wavefront four away
+    auto load_k = [&](int ti, const Lane<T>& L, int dw) {
       if (ti < nt)
-        tile_load_one<T>(X.kbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, lrow, L.kcol, voff, smem,
-                         T::K_OFF + ((ti >> 1) & 1) * T::BUF_B + (ti & 1) * T::TILE_B, wave);
+        tile_load_one<T>(X.kbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, L.lrow + dw * T::RPI, L.kcol,
+                         kvoff + (uint32_t)(dw * T::RPI) * (uint32_t)row_stride_b, smem,
+                         T::K_OFF + ((ti >> 1) & 1) * T::BUF_B + (ti & 1) * T::TILE_B, wave + dw);
     };
-    auto load_v = [&](int ti, int lrow, uint32_t voff, int wave) {
+    auto load_v = [&](int ti, const Lane<T>& L, int dw) {
       if (ti < nt)
-        tile_load_one<T>(X.vbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, lrow, L.vcol, voff, smem,
-                         T::V_OFF + ((ti >> 1) & 1) * T::BUF_B + (ti & 1) * T::TILE_B, wave);
-    };
-    auto load_pair = [&](int t, int lrow, uint32_t kvoff, uint32_t vvoff, int wave) {  // what phases 2t+2 / 2t+3 read
-      load_k(2 * t + 2, lrow, kvoff, wave);
-      load_k(2 * t + 3, lrow, kvoff, wave);
-      load_v(2 * t, lrow, vvoff, wave);
-      load_v(2 * t + 1, lrow, vvoff, wave);
+        tile_load_one<T>(X.vbase, row_stride_b, tile_first_key<T>(ti, kv_len), kv_len, L.lrow + dw * T::RPI, L.vcol,
+                         vvoff + (uint32_t)(dw * T::RPI) * (uint32_t)row_stride_b, smem,
+                         T::V_OFF + ((ti >> 1) & 1) * T::BUF_B + (ti & 1) * T::TILE_B, wave + dw);
     };
     // Inside the pair loop the group that is in its vector phase issues loads for both groups (its own rows and those
     // of the wavefront four away).  While the tiles are whole interior tiles (every tile but the last of a sequence)
@@ -169,41 +183,45 @@ attn_fwd_pp_kernel(AttnParams p) {
     auto load_k_pair_all = [&](int tp) {  // K tiles 2tp, 2tp+1 -> K buffer tp&1
       if (2 * tp + 1 < nt - 1) {
         const char* kp = X.kbase + (int64_t)(2 * tp) * T::BN * row_stride_b;
-        const uint32_t lk = (uint32_t)(uintptr_t)smem + T::K_OFF + (tp & 1) * T::BUF_B + (uint32_t)L.wave * 1024u;
+        const uint32_t lk = (uint32_t)(uintptr_t)smem + T::K_OFF + (tp & 1) * T::BUF_B + (uint32_t)wave * 1024u;
 #pragma unroll
         for (int j = 0; j < 2 * T::LPT; ++j) {
-          lds_dma_16(kp + j * round_b, L.kvoff, lk + j * T::NWAVES * 1024);
-          lds_dma_16(kp + j * round_b, L.kvoff + d4, lk + j * T::NWAVES * 1024 + other * 1024);
+          lds_dma_16(kp + j * round_b, kvoff, lk + j * T::NWAVES * 1024);
+          lds_dma_16(kp + j * round_b, kvoff + d4, lk + j * T::NWAVES * 1024 + other * 1024);
         }
       } else {
-        load_k(2 * tp, L.lrow, L.kvoff, L.wave);
-        load_k(2 * tp + 1, L.lrow, L.kvoff, L.wave);
-        load_k(2 * tp, L.lrow + other * T::RPI, L.kvoff + d4, L.wave + other);
-        load_k(2 * tp + 1, L.lrow + other * T::RPI, L.kvoff + d4, L.wave + other);
+        const Lane<T> L = fresh_lane();
+        load_k(2 * tp, L, 0);
+        load_k(2 * tp + 1, L, 0);
+        load_k(2 * tp, L, other);
+        load_k(2 * tp + 1, L, other);
       }
     };
     auto load_v_pair_all = [&](int tp) {  // V tiles 2tp, 2tp+1 -> V buffer tp&1
       if (2 * tp + 1 < nt - 1) {
         const char* vp = X.vbase + (int64_t)(2 * tp) * T::BN * row_stride_b;
-        const uint32_t lv = (uint32_t)(uintptr_t)smem + T::V_OFF + (tp & 1) * T::BUF_B + (uint32_t)L.wave * 1024u;
+        const uint32_t lv = (uint32_t)(uintptr_t)smem + T::V_OFF + (tp & 1) * T::BUF_B + (uint32_t)wave * 1024u;
 #pragma unroll
         for (int j = 0; j < 2 * T::LPT; ++j) {
-          lds_dma_16(vp + j * round_b, L.vvoff, lv + j * T::NWAVES * 1024);
-          lds_dma_16(vp + j * round_b, L.vvoff + d4, lv + j * T::NWAVES * 1024 + other * 1024);
+          lds_dma_16(vp + j * round_b, vvoff, lv + j * T::NWAVES * 1024);
+          lds_dma_16(vp + j * round_b, vvoff + d4, lv + j * T::NWAVES * 1024 + other * 1024);
         }
       } else {
-        load_v(2 * tp, L.lrow, L.vvoff, L.wave);
-        load_v(2 * tp + 1, L.lrow, L.vvoff, L.wave);
-        load_v(2 * tp, L.lrow + other * T::RPI, L.vvoff + d4, L.wave + other);
-        load_v(2 * tp + 1, L.lrow + other * T::RPI, L.vvoff + d4, L.wave + other);
+        const Lane<T> L = fresh_lane();
+        load_v(2 * tp, L, 0);
+        load_v(2 * tp + 1, L, 0);
+        load_v(2 * tp, L, other);
+        load_v(2 * tp + 1, L, other);
       }
     };
-    load_k(0, L.lrow, L.kvoff, L.wave);
-    load_k(1, L.lrow, L.kvoff, L.wave);
-    load_pair(0, L.lrow, L.kvoff, L.vvoff, L.wave);
-
     bf16x8 qf[T::NKS];
-    load_q<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, qf);
+    {
+      const Lane<T> L = fresh_lane();
+      for (int ti = 0; ti < 4; ++ti) load_k(ti, L, 0);  // K(P0), K(P1)
+      load_v(0, L, 0);                                  // V(P0)
+      load_v(1, L, 0);
+      load_q<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, qf);
+    }
 
     f32x16 o[T::NDB];
 #pragma unroll
@@ -215,7 +233,7 @@ attn_fwd_pp_kernel(AttnParams p) {
     f32x16 s[2][T::NKB];
     uint32_t pb[2][T::NKB][8];
     int ka[T::NKS], va[T::NDB];  // ka: K buffer the next QK reads; va: V buffer the next PV reads
-    L.operand_addrs((uint32_t)(uintptr_t)smem, (uint32_t)(uintptr_t)smem, ka, va);
+    fresh_lane().operand_addrs((uint32_t)(uintptr_t)smem, (uint32_t)(uintptr_t)smem, ka, va);
     float alpha1 = 1.f;
     uint64_t grown = 0;
 
@@ -233,8 +251,8 @@ attn_fwd_pp_kernel(AttnParams p) {
       if (t + 2 == npairs && tid == 0) s_item[par] = take_item(p);
       if (group == 1) load_v_pair_all(t + 1);            // read from phase 2t+4 on
       if (group == 0 && t >= 1) load_k_pair_all(t + 1);  // read from the next phase on (K(P1) came with the prologue)
-      tile_softmax<T, false, true>(s[0], L.hh, TailRows{0, T::BN}, c, pb[0], o, m_ref, l_run);
-      grown = tile_softmax<T, false, true, true>(s[1], L.hh, TailRows{0, T::BN}, c, pb[1], o, m_ref, l_run, &alpha1);
+      tile_softmax<T, false, true>(s[0], 0, TailRows{0, T::BN}, c, pb[0], o, m_ref, l_run);  // no mask: hh unused
+      grown = tile_softmax<T, false, true, true>(s[1], 0, TailRows{0, T::BN}, c, pb[1], o, m_ref, l_run, &alpha1);
       if (group == 0) wait_loads();
       wg_barrier();
       // ---- matrix phase: PV(Pt), QK(Pt+1)
@@ -252,8 +270,8 @@ attn_fwd_pp_kernel(AttnParams p) {
     }
     // ---- last pair: two tiles or one, the last of them masked; PV only
     if ((nt & 1) == 0) {
-      tile_softmax<T, false, true>(s[0], L.hh, TailRows{0, T::BN}, c, pb[0], o, m_ref, l_run);
-      grown = tile_softmax<T, true, true, true>(s[1], L.hh, tail_rows<T>(kv_len), c, pb[1], o, m_ref, l_run, &alpha1);
+      tile_softmax<T, false, true>(s[0], 0, TailRows{0, T::BN}, c, pb[0], o, m_ref, l_run);
+      grown = tile_softmax<T, true, true, true>(s[1], fresh_lane().hh, tail_rows<T>(kv_len), c, pb[1], o, m_ref, l_run, &alpha1);
       wg_barrier();
       __builtin_amdgcn_s_setprio(1);
       pp_stream<T, 2, 0, kPrefetch>(va, ka, pb, qf, o, s, grown, alpha1);
@@ -261,7 +279,7 @@ attn_fwd_pp_kernel(AttnParams p) {
       asm volatile("" : "+v"(l_run));  // the sums are taken here, not behind the barrier
       __builtin_amdgcn_s_setprio(0);
     } else {
-      tile_softmax<T, true, true>(s[0], L.hh, tail_rows<T>(kv_len), c, pb[0], o, m_ref, l_run);
+      tile_softmax<T, true, true>(s[0], fresh_lane().hh, tail_rows<T>(kv_len), c, pb[0], o, m_ref, l_run);
       wg_barrier();
       __builtin_amdgcn_s_setprio(1);
       pp_stream<T, 1, 0, kPrefetch>(va, ka, pb, qf, o, s, 0, 1.f);
@@ -271,7 +289,13 @@ attn_fwd_pp_kernel(AttnParams p) {
     }
     wg_barrier();
 
-    store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run, m_ref);
+    {
+      const Lane<T> L = fresh_lane();
+      int qrow = L.wave * 32 + L.l32;  // as in item_ctx
+      const bool row_valid = qrow < X.it.q_rows;
+      if (!row_valid) qrow = X.it.q_rows - 1;
+      store_out<T>(p, L, X.it, row_stride_b, X.head_off, qrow, row_valid, o, l_run, m_ref);
+    }
     if (group == 0) wg_barrier();  // group 0 idles (after its stores) while group 1 runs its last matrix phase
   }
   launch_clock_end(p, clock0);
