@@ -197,10 +197,10 @@ int dit_attn_sp_unpack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int6
  * image steps are short, video steps long):
  *     DIT_ATTN_KERNEL_AUTO   (-1) chosen per pack: the ping-pong kernel when
  *                                 its 256-row items fill the compute units,
- *                                 the 128-row kernel for packs with well
- *                                 under one such item per compute unit, whose
- *                                 last round would be under half full, or
- *                                 (cross-attention) with at most 640 keys per
+ *                                 the 128-row kernel for packs with under half
+ *                                 such an item per compute unit, whose second
+ *                                 round would be under 40 % full, or
+ *                                 (cross-attention) with at most 448 keys per
  *                                 item on average
  *     DIT_ATTN_KERNEL_128     (0) 128 query rows per tile
  *     DIT_ATTN_KERNEL_PINGPONG(1) 256 rows per tile, two alternating groups

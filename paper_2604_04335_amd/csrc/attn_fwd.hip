@@ -338,14 +338,16 @@ int attn_fwd_wgs_per_cu(AttnKernel kernel) { return kernel == AttnKernel::kIndep
 
 AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_k, int32_t n_seqs, int32_t n_heads,
                            int n_cus) {
-  // Measured on MI355X with equal-length sequences (time of the 128-row kernel over the ping-pong kernel, by 256-row
-  // items per compute unit): 0.5: 0.91;  0.75: 1.19;  0.94: 1.17;  1.0: 1.12;  1.25: 0.90;  1.5: 0.95;  1.6: 1.05;
-  // 1.9: 1.10;  2.0: 1.10;  2.5: 0.96;  3.0: 1.15;  3.2: 1.02;  4 and more: 1.05-1.09.  The ping-pong kernel is ahead
-  // whenever its items fill the compute units; the 128-row kernel, whose items are half as long, when there is well
-  // under one 256-row item per compute unit or when the last round of 256-row items would be less than half full.
-  // Items with few key tiles (cross-attention against a few hundred text keys) also run better on the 128-row kernel,
-  // whose workgroups have no idle phase at the ends of an item: 128 keys +17 %, 256 +9 %, 512 +3 %, 1024 -4 %.  (Packs
-  // of short self-attention sequences do not follow: 256 and 512 tokens -2 %, 640 +4 %, 768 -4 %; they stay as they are.)
+  // Measured on MI355X, head dimension 128 (time of the 128-row kernel over the ping-pong kernel, by 256-row items per
+  // compute unit; 4096-token sequences, 6 to 80 heads): 0.38: 0.99;  0.5: 1.03;  0.62: 1.30;  0.75: 1.23;  0.88: 1.18;
+  // 1.0: 1.16;  1.25: 0.98;  1.5: 1.01;  1.75: 1.11;  2.0: 1.13;  2.5: 1.09;  3.0: 1.22;  3.5: 1.07;  4 and more:
+  // 1.13-1.18; packs of 4352- and 1280-token sequences from 0.94 to 9.6 items per compute unit: 1.07-1.20.  The
+  // ping-pong kernel is ahead whenever its items fill the compute units; the 128-row kernel, whose items are half as
+  // long, when there is under half a 256-row item per compute unit, or (by 2 %) when a second round of 256-row items
+  // would be less than half full.
+  // Items with few key tiles (cross-attention against a few hundred text keys) run better on the 128-row kernel, whose
+  // workgroups have no idle phase at the ends of an item: 64 keys 0.91, 128: 0.90, 226: 0.93, 256: 0.94, 384: 0.96,
+  // 512: 1.00, 768: 1.05, 1024: 1.07, 2048: 1.11.
   // (Comparisons of two kernels must be made on a warm chip: in the first ~20 ms after idle, while the clocks still
   // ramp, whichever kernel runs second looks faster.)
   const int32_t* ck = cu_seqlens_k ? cu_seqlens_k : cu_seqlens;
@@ -357,10 +359,10 @@ AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_
     items256 += it;
     tiles += it * ((lk + 63) / 64);
   }
-  if (items256 * 8 < (int64_t)n_cus * 5) return AttnKernel::kIndependent128;
-  if (cu_seqlens_k != nullptr && tiles <= 10 * items256) return AttnKernel::kIndependent128;
-  const int64_t in_last_round = items256 % n_cus;
-  if (items256 <= 3 * (int64_t)n_cus && in_last_round != 0 && 2 * in_last_round <= n_cus) return AttnKernel::kIndependent128;
+  if (items256 * 20 < (int64_t)n_cus * 9) return AttnKernel::kIndependent128;
+  if (cu_seqlens_k != nullptr && tiles <= 7 * items256) return AttnKernel::kIndependent128;
+  const int64_t in_second_round = items256 - n_cus;
+  if (in_second_round > 0 && 5 * in_second_round <= 2 * (int64_t)n_cus) return AttnKernel::kIndependent128;
   return AttnKernel::kPingPong256;
 }
 

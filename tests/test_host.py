@@ -120,14 +120,14 @@ def test_bench_refuses_more_than_one_gpu():
 
 
 def test_kernel_choice_by_items_per_compute_unit():
-    """dit_attn_plan's block_m shows which kernel family a pack gets on a 256-CU device: the 128-row kernel for well
-    under one 256-row item per compute unit and for packs of at most three rounds whose last round would be under half
-    full, the 256-row (ping-pong) kernel otherwise.  4096 tokens are 16 items of 256 rows per head."""
+    """dit_attn_plan's block_m shows which kernel family a pack gets on a 256-CU device: the 128-row kernel for under
+    0.45 256-row items per compute unit and for packs whose second round of such items would be at most 40 % full,
+    the 256-row (ping-pong) kernel otherwise.  4096 tokens are 16 items of 256 rows per head."""
     def block_m(lens, heads):
         cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
         return da.dit_attn_plan(cu, heads, 128)[1]
-    expect = {8: 128, 9: 128, 10: 256, 12: 256, 16: 256, 17: 128, 20: 128, 24: 128, 25: 256, 32: 256, 40: 128, 41: 256,
-              48: 256, 49: 256, 64: 256}
+    expect = {6: 128, 7: 128, 8: 256, 9: 256, 10: 256, 12: 256, 16: 256, 17: 128, 20: 128, 22: 128, 23: 256, 24: 256, 25: 256,
+              32: 256, 40: 256, 41: 256, 48: 256, 49: 256, 64: 256}
     for heads, bm in expect.items():
         assert block_m([4096], heads) == bm, heads
     assert block_m([20506], 24) == 256
