@@ -32,9 +32,10 @@ DEFAULT_WORKLOAD = "mixed_varlen"
 # counter readings, the commands and the kernel build they were taken on).  A workload without a current profile
 # reports traffic null.
 MEASURED_HBM_BYTES = {
-    "mixed_varlen": (2_541_192_806, "profiles/attn_fwd_pp_kernel_mixed_varlen.md"),  # fetch 1089238.9 KiB x 2.000 + write 303155.8 KiB
-    "sp_shard": (4_419_153_408, "profiles/attn_fwd_pp_kernel_sp_shard.md"),          # fetch 2058975.5 KiB x 2.000 + write 197628.5 KiB
-    "t2v_single": (1_413_653_197, "profiles/attn_fwd_pp_kernel_t2v_single.md"),      # fetch 625092.8 KiB x 2.000 + write 130335.1 KiB
+    "mixed_varlen": (2_683_253_555, "profiles/attn_fwd_pp_kernel_mixed_varlen.md"),  # fetch 1161477.4 KiB x 2.000 + write 297410.0 KiB x 1.000
+    "sp_shard": (4_427_858_330, "profiles/attn_fwd_pp_kernel_sp_shard.md"),          # fetch 2065879.2 KiB x 2.000 + write 192322.0 KiB x 1.000
+    "t2v_single": (1_486_816_358, "profiles/attn_fwd_pp_kernel_t2v_single.md"),      # fetch 663314.8 KiB x 2.000 + write 125339.5 KiB x 1.000
+    "t2i_batch": (1_055_838_413, "profiles/attn_fwd_pp_kernel_t2i_batch.md"),        # fetch 462300.8 KiB x 2.000 + write 106490.6 KiB x 1.000
 }
 # The second configuration that the benchmark definition holds to the 50 % target; timed in the default run as well
 # and reported under "second_target_config" (the headline `value` stays DEFAULT_WORKLOAD's).
@@ -332,7 +333,7 @@ def main():
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--split-kv", type=int, default=1,
                     help="let small packs split every sequence's keys into up to this many chunks (dit_attn_set_split_kv)")
-    ap.add_argument("--op", default="attn", choices=["attn", "merge", "cross", "layout", "sched"],
+    ap.add_argument("--op", default="attn", choices=["attn", "merge", "cross", "layout", "sched", "ceiling"],
                     help="attn: the denoising-step self-attention (the headline line); merge / cross: one line for the "
                          "partial-result merge kernel (HBM bound) or for cross-attention against text keys")
     ap.add_argument("--kernel", default="auto", choices=["auto", "128", "pingpong"],
@@ -352,6 +353,22 @@ def main():
 
     if args.op == "sched":
         print(json.dumps(bench_sched()), flush=True)
+        return
+    if args.op == "ceiling":
+        # The register-only MFMA loops of the measurement aid, every mix: what the matrix pipes give alone and beside
+        # the LDS reads and vector instructions of an attention tile (no barriers, no memory loads, no dependences).
+        probe = load_probe()
+        if probe is None:
+            print("bench.py: libdit_probe.so has not been built", file=sys.stderr)
+            sys.exit(3)
+        names = ["mfma_only", "pingpong_mix", "lds_reads_only", "vector_instructions_only", "half_lds_two_waves_per_simd",
+                 "half_lds_one_wave_per_simd"]
+        mixes = {}
+        for mix, name in enumerate(names):
+            tf, mhz = probe(mix, 20, 20)
+            mixes[name] = {"tflops": round(tf, 1), "shader_clock_mhz": round(mhz, 1), "pct_of_mfma_peak": round(100 * tf / MFMA_BF16_PEAK_TFLOPS, 2)}
+        print(json.dumps({"metric": "register-only MFMA loops (measurement aid), TFLOP/s", "unit": "TFLOP/s", "n_gpus": 1,
+                          "peak": MFMA_BF16_PEAK_TFLOPS, "mixes": mixes}), flush=True)
         return
 
     import torch
