@@ -214,6 +214,33 @@ attn_fwd_pp_kernel(AttnParams p) {
         load_v(2 * tp + 1, L, other);
       }
     };
+    // A wavefront none of whose 32 query rows exists (the ragged last query tile of a sequence, a half-height item of
+    // a pack's last round) takes its part in the loads and barriers of the item and computes nothing: its SIMD and the
+    // power it would draw go to the wavefront it shares the SIMD with.  Wavefront 0 always has rows.
+    if (wave * 32 >= X.it.q_rows) {
+      {
+        const Lane<T> L = fresh_lane();
+        for (int ti = 0; ti < 4; ++ti) load_k(ti, L, 0);
+        load_v(0, L, 0);
+        load_v(1, L, 0);
+      }
+      wait_loads();
+      wg_barrier();
+      if (group == 1) wg_barrier();
+      wg_barrier();
+      for (int t = 0; t + 1 < npairs; ++t) {
+        if (group == 1) load_v_pair_all(t + 1);
+        if (group == 0 && t >= 1) load_k_pair_all(t + 1);
+        if (group == 0) wait_loads();
+        wg_barrier();
+        if (group == 1) wait_loads();
+        wg_barrier();
+      }
+      wg_barrier();
+      wg_barrier();
+      if (group == 0) wg_barrier();
+      continue;
+    }
     bf16x8 qf[T::NKS];
     {
       const Lane<T> L = fresh_lane();
