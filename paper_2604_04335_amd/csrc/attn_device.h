@@ -50,6 +50,10 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
 typedef __attribute__((address_space(3))) char lds_char;
+// The slot through which a workgroup's wavefronts learn the index of their next item.  Typed as LDS memory on purpose:
+// through a generic pointer the read is a flat load, which the hardware counts with the vector-memory operations, and
+// the wait for it at the top of an item then also waits for every output store of the item before.
+typedef __attribute__((address_space(3))) volatile uint32_t lds_slot;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 typedef __attribute__((address_space(1))) const void gptr_void;
@@ -589,13 +593,19 @@ __device__ __forceinline__ void launch_clock_end(const AttnParams& p, const Laun
 struct ItemU {
   int q_start, kv_start, kv_len, head, q_rows, part;
 };
+// The record comes through a scalar load (idx is the same in every lane): scalar loads are counted apart from the
+// vector-memory operations, so the first thing an item does is not a wait for the output stores of the item before it
+// (a vector load here cost a wavefront 3 000 to 6 000 cycles per item).  The list is written before the launch (by the
+// host or by the kernel before this one on the stream) and never during it.
 __device__ __forceinline__ ItemU fetch_item(const WorkItem* items, uint32_t idx) {
-  const WorkItem it = items[idx];
+  const WorkItem* rec = items + idx;
+  u32x4 w;
+  asm volatile("s_load_dwordx4 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(w) : "s"(rec) : "memory");
   ItemU u;
-  u.q_start = __builtin_amdgcn_readfirstlane(it.q_start);
-  u.kv_start = __builtin_amdgcn_readfirstlane(it.kv_start);
-  u.kv_len = __builtin_amdgcn_readfirstlane(it.kv_len);
-  const int rh = __builtin_amdgcn_readfirstlane(it.rows_head);
+  u.q_start = (int)w[0];
+  u.kv_start = (int)w[1];
+  u.kv_len = (int)w[2];
+  const int rh = (int)w[3];
   u.head = rh & 0xFFFF;
   u.q_rows = (rh >> 16) & 0xFFF;
   u.part = (rh >> 28) & 0xF;
@@ -616,14 +626,21 @@ __device__ __forceinline__ void load_q(const AttnParams& p, const Lane<T>& L, co
 }
 
 // Epilogue: O^T / l -> bf16 -> out, and, if asked for, lse = ln sum_j exp(scale * s_j) = ln 2 * (c * m + log2 l).
-// Lane holds d = 32*db + 8*g + 4*hh + j (i = 4*g + j) of query l32.
+// Lane holds d = 32*db + 8*g + 4*hh + j (i = 4*g + j) of query l32: eight bytes of each of 32 rows per store
+// instruction if stored from there, 32 partly written cache lines each time, sixteen times per wavefront.  That cost
+// 4 % of an item of 4352 keys and 29 % of a cross-attention item of 512 keys (measured by leaving the stores out).  The
+// rows therefore go through `stage`, 32 * ROW_B bytes of LDS that belong to this wavefront at this point (the caller
+// names a K / V buffer that nobody reads or loads into until the next barrier): written in the accumulator layout,
+// 16-byte chunk c of row r at chunk c ^ (r mod chunks per row) so that the 32 rows of a write spread over the banks,
+// and read back as whole rows, so that a store instruction writes 1 KB of whole rows (four rows at head dimension 128).
 template <class T>
 __device__ __forceinline__ void store_out(const AttnParams& p, const Lane<T>& L, const ItemU& it, int64_t row_stride_b,
                                           int64_t head_off, int qrow, bool row_valid, const f32x16 (&o)[T::NDB],
-                                          float l_run, float m_ref) {
+                                          float l_run, float m_ref, uint32_t stage) {
   const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (row_valid && p.part_out != nullptr) {
+  if (p.part_out != nullptr) {
     // split-KV: this item saw one chunk of the keys; its normalised result and lse go to the workspace in fp32
+    if (!row_valid) return;
     const float inv = 1.0f / l_tot;
     const int64_t rh = ((int64_t)it.part * p.part_rows + it.q_start + qrow) * p.n_heads + it.head;
     float* optr = p.part_out + rh * T::D + L.hh * 4;
@@ -638,9 +655,14 @@ __device__ __forceinline__ void store_out(const AttnParams& p, const Lane<T>& L,
     if (L.hh == 0) p.part_lse[rh] = 0.69314718055994530942f * (m_ref * p.c_log2 + __builtin_amdgcn_logf(l_tot));
     return;
   }
-  if (row_valid) {
-    const float inv = 1.0f / l_tot;
-    char* optr = static_cast<char*>(p.out) + (int64_t)(it.q_start + qrow) * row_stride_b + head_off + L.hh * 8;
+  {
+    typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
+    typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+    constexpr int CH = T::ROW_B / 16;  // 16-byte chunks of a row
+    static_assert(4 * T::NDB == CH && 64 % CH == 0, "a row is NDB blocks of four chunks");
+    const float inv = 1.0f / l_tot;  // rows past the end of a ragged tile hold a copy of the last row: finite, not stored
+    const uint32_t wr = stage + (uint32_t)(L.l32 * T::ROW_B + L.hh * 8);
+    const uint32_t wsw = (uint32_t)(L.l32 & (CH - 1)) * 16u;
 #pragma unroll
     for (int db = 0; db < T::NDB; ++db)
 #pragma unroll
@@ -648,9 +670,28 @@ __device__ __forceinline__ void store_out(const AttnParams& p, const Lane<T>& L,
         u32x2 w;
         w[0] = pack_bf16x2(o[db][4 * g + 0] * inv, o[db][4 * g + 1] * inv);
         w[1] = pack_bf16x2(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
-        *reinterpret_cast<u32x2*>(optr + (32 * db + 8 * g) * 2) = w;
+        *(lds_u32x2*)(uintptr_t)(wr + ((uint32_t)((4 * db + g) * 16) ^ wsw)) = w;
       }
-    if (p.lse != nullptr && L.hh == 0)
+    // LDS serves a wavefront's instructions in order: the reads below see the writes above, of other lanes too.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+    constexpr int RPS = 64 / CH;  // rows per store instruction
+    const int ch = L.lane & (CH - 1), r0 = L.lane / CH;
+    const int row0 = L.wave * 32 + r0;  // row of the item's query tile
+    char* optr = static_cast<char*>(p.out) + (int64_t)(it.q_start + row0) * row_stride_b + head_off + ch * 16;
+    u32x4 w[32 / RPS];
+#pragma unroll
+    for (int i = 0; i < 32 / RPS; ++i) {
+      const int r = r0 + i * RPS;
+      w[i] = *(lds_u32x4*)(uintptr_t)(stage + (uint32_t)(r * T::ROW_B + ((ch ^ (r & (CH - 1))) * 16)));
+    }
+#pragma unroll
+    for (int i = 0; i < 32 / RPS; ++i) asm volatile("" : "+v"(w[i]));  // all reads are issued before the first store
+    const int n_valid = it.q_rows - row0;
+#pragma unroll
+    for (int i = 0; i < 32 / RPS; ++i)
+      if (i * RPS < n_valid) *reinterpret_cast<u32x4*>(optr + (int64_t)(i * RPS) * row_stride_b) = w[i];
+    if (row_valid && p.lse != nullptr && L.hh == 0)
       p.lse[(int64_t)(it.q_start + qrow) * p.n_heads + it.head] = 0.69314718055994530942f * (m_ref * p.c_log2 + __builtin_amdgcn_logf(l_tot));
   }
 }

@@ -14,7 +14,7 @@ __global__ void __attribute__((amdgpu_flat_work_group_size(T::NT, T::NT), amdgpu
 attn_fwd_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
   lds_char* smem = (lds_char*)smem_generic;
-  volatile uint32_t* s_item = reinterpret_cast<volatile uint32_t*>(smem_generic + T::ITEM_OFF);
+  lds_slot* s_item = reinterpret_cast<lds_slot*>(smem + T::ITEM_OFF);
 
   const LaunchClock clock0 = launch_clock_begin();
   const int tid = threadIdx.x;
@@ -63,11 +63,17 @@ attn_fwd_kernel(AttnParams p) {
       // reading the other buffers (tile t-1), so they can be refilled with tile t+1 while tile t is used.
       wait_loads();
       wg_barrier();
-      if (t + 2 == nt && tid == 0) s_item[par] = take_item(p);  // visible after the barrier of the last tile
+      // The next index is requested here and put into its slot at the end of the tile (visible after the barrier of
+      // the last tile): the request takes about a microsecond to come back, which thread 0's wavefront spends on
+      // the tile instead of waiting.
+      const bool ask = t + 2 == nt && tid == 0;
+      uint32_t next_item = 0;
+      if (ask) next_item = take_item(p);
       load_tile(t + 1);
       mfma_stream<T, false, 0, T::NQK, kPrefetch>(smem, va, ka, pb, qf, o, s);
       tile_softmax<T, false>(s, L.hh, TailRows{0, T::BN}, c, pb, o, m_ref, l_run);
       mfma_stream<T, true, 0, 0, kPrefetch>(smem, va, ka, pb, qf, o, s);
+      if (ask) s_item[par] = next_item;
 #pragma unroll
       for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::TILE_B;
 #pragma unroll
@@ -80,7 +86,12 @@ attn_fwd_kernel(AttnParams p) {
     tile_softmax<T, true>(s, L.hh, tail_rows<T>(kv_len), c, pb, o, m_ref, l_run);
     mfma_stream<T, true, 0, 0, kPrefetch>(smem, va, ka, pb, qf, o, s);
 
-    store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run, m_ref);
+    // The rows are staged in the buffers of the parity that the last tile does not use: every wavefront is done with
+    // tile nt - 2 (the barrier of the last tile), nothing is being loaded there, and the next item's loads come after
+    // the barrier below.  Wavefronts 0, 1 take the K buffer of that parity, wavefronts 2, 3 the V buffer.
+    const uint32_t stage = (uint32_t)(uintptr_t)smem + (L.wave < 2 ? T::K_OFF : T::V_OFF) + (nt & 1) * T::TILE_B +
+                           (uint32_t)(L.wave & 1) * (32 * T::ROW_B);
+    store_out<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, X.row_valid, o, l_run, m_ref, stage);
     wg_barrier();  // the next item's first loads overwrite the buffers of parity 0
   }
   launch_clock_end(p, clock0);
@@ -117,7 +128,7 @@ attn_fwd_pp_kernel(AttnParams p) {
   static_assert(T::NWAVES == 8 && T::SUBS == 2, "two groups of four wavefronts, two tiles per phase");
   extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
   lds_char* smem = (lds_char*)smem_generic;
-  volatile uint32_t* s_item = reinterpret_cast<volatile uint32_t*>(smem_generic + T::ITEM_OFF);
+  lds_slot* s_item = reinterpret_cast<lds_slot*>(smem + T::ITEM_OFF);
 
   const LaunchClock clock0 = launch_clock_begin();
   const int tid = threadIdx.x;
@@ -275,12 +286,18 @@ attn_fwd_pp_kernel(AttnParams p) {
     if (npairs == 1 && tid == 0) s_item[par] = take_item(p);  // two barriers follow in the last pair
     for (int t = 0; t + 1 < npairs; ++t) {
       // ---- vector phase: softmax of both tiles of pair t (whole tiles)
-      if (t + 2 == npairs && tid == 0) s_item[par] = take_item(p);
+      // The next index is requested at the start of this phase and put into its slot at the end (visible after the
+      // barriers of the last pair): the request takes about a microsecond, which thread 0's wavefront spends on its
+      // softmaxes instead of waiting while seven wavefronts wait for it at the barrier.
+      const bool ask = t + 2 == npairs && tid == 0;
+      uint32_t next_item = 0;
+      if (ask) next_item = take_item(p);
       if (group == 1) load_v_pair_all(t + 1);            // read from phase 2t+4 on
       if (group == 0 && t >= 1) load_k_pair_all(t + 1);  // read from the next phase on (K(P1) came with the prologue)
       tile_softmax<T, false, true>(s[0], 0, TailRows{0, T::BN}, c, pb[0], o, m_ref, l_run);  // no mask: hh unused
       grown = tile_softmax<T, false, true, true>(s[1], 0, TailRows{0, T::BN}, c, pb[1], o, m_ref, l_run, &alpha1);
       if (group == 0) wait_loads();
+      if (ask) s_item[par] = next_item;
       wg_barrier();
       // ---- matrix phase: PV(Pt), QK(Pt+1)
       __builtin_amdgcn_s_setprio(1);
@@ -321,7 +338,13 @@ attn_fwd_pp_kernel(AttnParams p) {
       int qrow = L.wave * 32 + L.l32;  // as in item_ctx
       const bool row_valid = qrow < X.it.q_rows;
       if (!row_valid) qrow = X.it.q_rows - 1;
-      store_out<T>(p, L, X.it, row_stride_b, X.head_off, qrow, row_valid, o, l_run, m_ref);
+      // Staging area of the rows.  Group 0 stores while group 1 runs its last matrix phase, which reads V only, and
+      // every load of K has been awaited: it takes K buffer 0.  Group 1 stores while group 0 starts the next item and
+      // loads its first tiles into both K buffers and V buffer 0: it takes V buffer 1, which is loaded into next by
+      // group 1 itself, in the next item's pair loop behind two barriers.
+      const uint32_t stage = (uint32_t)(uintptr_t)smem + (group == 0 ? T::K_OFF : T::V_OFF + T::BUF_B) +
+                             (uint32_t)(wave & 3) * (32 * T::ROW_B);
+      store_out<T>(p, L, X.it, row_stride_b, X.head_off, qrow, row_valid, o, l_run, m_ref, stage);
     }
     if (group == 0) wg_barrier();  // group 0 idles (after its stores) while group 1 runs its last matrix phase
   }
