@@ -690,7 +690,8 @@ __device__ __forceinline__ void store_out(const AttnParams& p, const Lane<T>& L,
     const int n_valid = it.q_rows - row0;
 #pragma unroll
     for (int i = 0; i < 32 / RPS; ++i)
-      if (i * RPS < n_valid) *reinterpret_cast<u32x4*>(optr + (int64_t)(i * RPS) * row_stride_b) = w[i];
+      if (i * RPS < n_valid)  // streaming stores: the rows are not read again by this call
+        __builtin_nontemporal_store(w[i], reinterpret_cast<u32x4*>(optr + (int64_t)(i * RPS) * row_stride_b));
     if (row_valid && p.lse != nullptr && L.hh == 0)
       p.lse[(int64_t)(it.q_start + qrow) * p.n_heads + it.head] = 0.69314718055994530942f * (m_ref * p.c_log2 + __builtin_amdgcn_logf(l_tot));
   }
