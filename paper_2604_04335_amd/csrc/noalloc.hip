@@ -29,7 +29,8 @@ struct PackArg {
 };
 
 // The list that plan_build makes on the host (sequences by descending length, ties in pack order; inside a sequence
-// heads are the slow index and query tiles the fast one), written by one workgroup.
+// heads are the slow index and whole query tiles the fast one, then the ragged last tile of every head), written by
+// one workgroup.
 __global__ void __launch_bounds__(256) noalloc_plan_kernel(PackArg pack, int32_t n_heads, int32_t block_m, WorkItem* items,
                                                            uint32_t* sync, uint32_t n_items) {
   __shared__ int32_t order[kNoAllocMaxSeqs];
@@ -63,9 +64,10 @@ __global__ void __launch_bounds__(256) noalloc_plan_kernel(PackArg pack, int32_t
     while (j + 1 < kNoAllocMaxSeqs && first[j + 1] <= idx) ++j;
     const int32_t seq = order[j];
     const int32_t start = pack.cu[seq], len = pack.cu[seq + 1] - start;
-    const uint32_t tiles = static_cast<uint32_t>((len + block_m - 1) / block_m);
-    const uint32_t local = idx - first[j];
-    const int32_t head = static_cast<int32_t>(local / tiles), m0 = static_cast<int32_t>(local % tiles) * block_m;
+    const uint32_t whole = static_cast<uint32_t>(len / block_m);  // whole query tiles per head
+    const uint32_t local = idx - first[j], n_whole = whole * static_cast<uint32_t>(n_heads);
+    const int32_t head = static_cast<int32_t>(local < n_whole ? local / whole : local - n_whole);
+    const int32_t m0 = static_cast<int32_t>(local < n_whole ? local % whole : whole) * block_m;
     const int32_t rows = len - m0 < block_m ? len - m0 : block_m;
     items[idx] = WorkItem{start + m0, start, len, (rows << 16) | head};
   }

@@ -41,13 +41,19 @@ void plan_build_cross(const int32_t* cu_q, const int32_t* cu_k, int32_t n_seqs, 
     const int32_t tiles = (k_len + block_n - 1) / block_n;
     const int32_t tiles_per_part = (tiles + n_splits - 1) / n_splits;
     const int32_t chunk = tiles_per_part * block_n;
-    for (int32_t h = 0; h < n_heads; ++h) {
-      for (int32_t m0 = 0; m0 < q_len; m0 += block_m) {
-        const int32_t rows = std::min(block_m, q_len - m0);
-        for (int32_t part = 0, kb = 0; kb < k_len; ++part, kb += chunk)
-          items.push_back(WorkItem{q0 + m0, k0 + kb, std::min(chunk, k_len - kb), (part << 28) | (rows << 16) | h});
-      }
-    }
+    auto push_tile = [&](int32_t h, int32_t m0) {
+      const int32_t rows = std::min(block_m, q_len - m0);
+      for (int32_t part = 0, kb = 0; kb < k_len; ++part, kb += chunk)
+        items.push_back(WorkItem{q0 + m0, k0 + kb, std::min(chunk, k_len - kb), (part << 28) | (rows << 16) | h});
+    };
+    // Whole query tiles of all heads first, then the ragged last tile of every head: a ragged tile is quicker (its
+    // wavefronts without rows compute nothing), and a workgroup that gets ahead of the others in the middle of a
+    // sequence streams K and V on its own from then on instead of sharing them in L2 with the workgroups beside it.
+    const int32_t whole = q_len / block_m * block_m;
+    for (int32_t h = 0; h < n_heads; ++h)
+      for (int32_t m0 = 0; m0 < whole; m0 += block_m) push_tile(h, m0);
+    if (whole < q_len)
+      for (int32_t h = 0; h < n_heads; ++h) push_tile(h, whole);
   }
 }
 

@@ -25,7 +25,8 @@ int plan_validate(const int32_t* cu_seqlens, int32_t n_seqs);
 
 // Build the ordered work-list.  Longest sequences first (their tiles cost the
 // most); inside a sequence, heads are the slow index and query tiles the fast
-// one, so workgroups running side by side stream the same K/V rows.
+// one, so workgroups running side by side stream the same K/V rows; the ragged
+// last query tile of every head comes after the sequence's whole tiles.
 void plan_build(const int32_t* cu_seqlens, int32_t n_seqs, int32_t n_heads, int32_t block_m,
                 std::vector<WorkItem>& items);
 
