@@ -254,11 +254,12 @@ attn_fwd_pp_kernel(AttnParams p) {
     }
     bf16x8 qf[T::NKS];
     {
+      // Q first: its rows come from memory (no compute unit has read them before), K and V mostly from L2
       const Lane<T> L = fresh_lane();
+      load_q<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, qf);
       for (int ti = 0; ti < 4; ++ti) load_k(ti, L, 0);  // K(P0), K(P1)
       load_v(0, L, 0);                                  // V(P0)
       load_v(1, L, 0);
-      load_q<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, qf);
     }
 
     f32x16 o[T::NDB];

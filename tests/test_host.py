@@ -79,6 +79,23 @@ def test_plan_covers_every_row_once(lens, H, D):
     assert len(items) == expect
 
 
+def test_plan_puts_ragged_tiles_behind_the_whole_tiles_of_their_sequence():
+    """Inside a sequence: heads slow and whole query tiles fast (neighbouring workgroups stream the same K/V rows), then
+    the ragged last tile of every head (a quicker item, which would take its workgroup out of step with its
+    neighbours in the middle of the sequence)."""
+    lens, H = [1000, 600], 3
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    items, bm = da.dit_attn_plan(cu, H, 128)
+    for s, L in enumerate(lens):
+        mine = items[items[:, 1] == cu[s]]
+        whole, rows = L // bm, mine[:, 3] >> 16
+        assert np.all(rows[:whole * H] == bm) and np.all(rows[whole * H:] == L - whole * bm)
+        assert list(mine[:whole * H, 3] & 0xFFFF) == [h for h in range(H) for _ in range(whole)]
+        assert list(mine[:whole * H, 0] - cu[s]) == [t * bm for _ in range(H) for t in range(whole)]
+        assert list(mine[whole * H:, 3] & 0xFFFF) == list(range(H))
+        assert np.all(mine[whole * H:, 0] - cu[s] == whole * bm)
+
+
 def test_plan_is_independent_of_packing():
     # a sequence's tiles (relative to its start) do not depend on its neighbours
     a, bm = da.dit_attn_plan(np.array([0, 300], dtype=np.int32), 2, 128)
