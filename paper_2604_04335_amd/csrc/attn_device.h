@@ -26,6 +26,9 @@
 // distinct banks.  The swizzle is applied by choosing which global chunk a lane
 // fetches, so it costs nothing.
 //
+// Epilogue.  In the accumulator layout a lane holds eight bytes of one output row, so the rows are staged through a K
+// or V buffer that is free at the end of an item and leave as whole rows (store_out).
+//
 // Softmax reference.  The value subtracted in the exponent follows a row's running maximum lazily: it moves (and O^T
 // and the running sum are rescaled) only in tiles where the row's maximum exceeds it by more than 2^8 in the base-2
 // exponent, so probabilities lie in (0, 2^8] rather than (0, 1]; the quotient O / l does not depend on the reference.
