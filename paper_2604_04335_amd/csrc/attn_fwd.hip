@@ -229,19 +229,18 @@ attn_fwd_pp_kernel(AttnParams p) {
     // a pack's last round) takes its part in the loads and barriers of the item and computes nothing: its SIMD and the
     // power it would draw go to the wavefront it shares the SIMD with.  Wavefront 0 always has rows.
     if (wave * 32 >= X.it.q_rows) {
-      {
-        const Lane<T> L = fresh_lane();
-        for (int ti = 0; ti < 4; ++ti) load_k(ti, L, 0);
-        load_v(0, L, 0);
-        load_v(1, L, 0);
-      }
+      if (group == 0) load_k_pair_all(0);
       wait_loads();
       wg_barrier();
-      if (group == 1) wg_barrier();
+      if (group == 1) {
+        load_v_pair_all(0);
+        wg_barrier();
+        wait_loads();
+      }
       wg_barrier();
       for (int t = 0; t + 1 < npairs; ++t) {
         if (group == 1) load_v_pair_all(t + 1);
-        if (group == 0 && t >= 1) load_k_pair_all(t + 1);
+        if (group == 0) load_k_pair_all(t + 1);
         if (group == 0) wait_loads();
         wg_barrier();
         if (group == 1) wait_loads();
@@ -254,12 +253,15 @@ attn_fwd_pp_kernel(AttnParams p) {
     }
     bf16x8 qf[T::NKS];
     {
-      // Q first: its rows come from memory (no compute unit has read them before), K and V mostly from L2
-      const Lane<T> L = fresh_lane();
-      load_q<T>(p, L, X.it, row_stride_b, X.head_off, X.qrow, qf);
-      for (int ti = 0; ti < 4; ++ti) load_k(ti, L, 0);  // K(P0), K(P1)
-      load_v(0, L, 0);                                  // V(P0)
-      load_v(1, L, 0);
+      // Only what phase 0 needs, Q and K(P0): the loads of an item's start and the stores of its end go through the
+      // compute unit's one path to L2 at some 30 bytes a cycle, and Q, three pairs of tiles and the output rows there
+      // at once (224 KB) were 7 500 cycles of every item.  V(P0) and K(P1), first read in phase 2, follow in phases 0
+      // and 1, when that path is idle.  Q first: its rows come from memory (no compute unit has read them before), K
+      // and V mostly from L2.
+      // K(P0) is loaded by group 0 for both groups: group 1, which comes out of the item before a phase later and
+      // with its output stores just issued, is what the first barrier waits for.
+      load_q<T>(p, fresh_lane(), X.it, row_stride_b, X.head_off, X.qrow, qf);
+      if (group == 0) load_k_pair_all(0);
     }
 
     f32x16 o[T::NDB];
@@ -277,11 +279,15 @@ attn_fwd_pp_kernel(AttnParams p) {
     uint64_t grown = 0;
 
     wait_loads();
-    wg_barrier();                  // K(P0), K(P1), V(P0) of every wave have landed; phase 0 starts
-    if (group == 1) wg_barrier();  // group 1 idles in phase 0
+    wg_barrier();  // Q and K(P0) of every wave have landed; phase 0 starts
+    if (group == 1) {  // group 1 has no matrix work in phase 0: it requests V(P0), awaited behind its QK(P0)
+      load_v_pair_all(0);
+      wg_barrier();
+    }
     pp_stream<T, 0, 2, kPrefetch>(va, ka, pb, qf, o, s, 0, 1.f);  // QK(P0)
 #pragma unroll
     for (int ks = 0; ks < T::NKS; ++ks) ka[ks] ^= T::BUF_B;
+    if (group == 1) wait_loads();
     wg_barrier();
 
     if (npairs == 1 && tid == 0) s_item[par] = take_item(p);  // two barriers follow in the last pair
@@ -294,7 +300,7 @@ attn_fwd_pp_kernel(AttnParams p) {
       uint32_t next_item = 0;
       if (ask) next_item = take_item(p);
       if (group == 1) load_v_pair_all(t + 1);            // read from phase 2t+4 on
-      if (group == 0 && t >= 1) load_k_pair_all(t + 1);  // read from the next phase on (K(P1) came with the prologue)
+      if (group == 0) load_k_pair_all(t + 1);  // read from the next phase on
       tile_softmax<T, false, true>(s[0], 0, TailRows{0, T::BN}, c, pb[0], o, m_ref, l_run);  // no mask: hh unused
       grown = tile_softmax<T, false, true, true>(s[1], 0, TailRows{0, T::BN}, c, pb[1], o, m_ref, l_run, &alpha1);
       if (group == 0) wait_loads();
