@@ -200,7 +200,7 @@ int dit_attn_sp_unpack_heads(dit_attn_ctx* ctx, const void* src, void* dst, int6
  *                                 the 128-row kernel for packs with under half
  *                                 such an item per compute unit, whose second
  *                                 round would be under 40 % full, or
- *                                 (cross-attention) with at most 448 keys per
+ *                                 (cross-attention) with at most 320 keys per
  *                                 item on average
  *     DIT_ATTN_KERNEL_128     (0) 128 query rows per tile
  *     DIT_ATTN_KERNEL_PINGPONG(1) 256 rows per tile, two alternating groups

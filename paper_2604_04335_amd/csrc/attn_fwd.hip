@@ -403,8 +403,8 @@ AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_
   // long, when there is under half a 256-row item per compute unit, or (by 2 %) when a second round of 256-row items
   // would be less than half full.
   // Items with few key tiles (cross-attention against a few hundred text keys) run better on the 128-row kernel, whose
-  // workgroups have no idle phase at the ends of an item: 64 keys 0.91, 128: 0.90, 226: 0.93, 256: 0.94, 384: 0.96,
-  // 512: 1.00, 768: 1.05, 1024: 1.07, 2048: 1.11.
+  // workgroups have no idle phase at the ends of an item: 64 keys 0.83, 128: 0.89, 226: 0.96, 256: 0.96, 384: 1.02,
+  // 512: 1.04, 768: 1.07, 1024: 1.05, 2048: 1.09.
   // (Comparisons of two kernels must be made on a warm chip: in the first ~20 ms after idle, while the clocks still
   // ramp, whichever kernel runs second looks faster.)
   const int32_t* ck = cu_seqlens_k ? cu_seqlens_k : cu_seqlens;
@@ -417,7 +417,7 @@ AttnKernel attn_fwd_select(const int32_t* cu_seqlens, const int32_t* cu_seqlens_
     tiles += it * ((lk + 63) / 64);
   }
   if (items256 * 20 < (int64_t)n_cus * 9) return AttnKernel::kIndependent128;
-  if (cu_seqlens_k != nullptr && tiles <= 7 * items256) return AttnKernel::kIndependent128;
+  if (cu_seqlens_k != nullptr && tiles <= 5 * items256) return AttnKernel::kIndependent128;
   const int64_t in_second_round = items256 - n_cus;
   if (in_second_round > 0 && 5 * in_second_round <= 2 * (int64_t)n_cus) return AttnKernel::kIndependent128;
   return AttnKernel::kPingPong256;
